@@ -1,0 +1,207 @@
+/*
+ * ls_attn.h -- C ABI of the MI355X (gfx950) hybrid tree attention library.
+ *
+ * The operation is the verification-time attention of LongSpec (arXiv 2502.17421,
+ * Section 3.3 "Hybrid Tree Attention"; correctness in the appendix "Correctness for
+ * Attention Aggregation"):
+ *
+ *   Every token of the speculation tree attends to
+ *     - all cached key/value rows of the main sequence, with no mask, and
+ *     - the tree tokens on its own root path (itself included), i.e. under the
+ *       tree mask,
+ *   the two parts are computed separately, each returning a normalised output O and the
+ *   log-sum-exp LSE of its scaled logits, and are then combined by
+ *       LSE_merge = log(exp(LSE_a) + exp(LSE_b))
+ *       O_merge   = O_a exp(LSE_a - LSE_merge) + O_b exp(LSE_b - LSE_merge),
+ *   which equals one softmax attention over the concatenated keys.
+ *
+ * The cached part is itself split along the key axis (the "Flash Attention" the paper
+ * calls is the split-KV decoding kernel, see the footnote in Section 1); the same merge
+ * rule, applied to n_splits + 1 partial results, joins everything.
+ *
+ * Conventions for every entry point
+ *   - Returns LS_OK (0) or a negative ls_status.  No exceptions, no abort.
+ *   - Pointers marked DEVICE are device memory owned by the caller; the library
+ *     neither allocates nor frees device memory and keeps no device state.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream) and the call returns without synchronising.
+ *   - Argument errors are found on the host before anything is launched.  A launch
+ *     failure reported by HIP maps to LS_ERR_HIP.
+ *   - The same inputs give bit-identical outputs (fixed split schedule, no float
+ *     atomics).
+ *   - Calls are re-entrant; concurrency is by streams.  Calls sharing a workspace or
+ *     output buffer must be ordered by the caller.
+ *
+ * Tensor layouts.  The last (head_dim) axis is contiguous.  Other axes are addressed
+ * through element strides in ls_desc, so both [B,H,L,D] and [B,L,H,D] storage work.
+ * Every row start must be 16-byte aligned (base pointers and strides*sizeof(elem)
+ * multiples of 16).
+ *   q        [batch, n_q_heads,  n_tree,      head_dim]   dtype
+ *   k_cache  [batch, n_kv_heads, >=prefix_len, head_dim]  dtype   (v_cache alike)
+ *   k_tree   [batch, n_kv_heads, n_tree,      head_dim]   dtype   (v_tree alike)
+ *   out      [batch, n_q_heads,  n_tree,      head_dim]   dtype
+ *   lse      [batch, n_q_heads,  n_tree]                  float, contiguous
+ * Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *
+ * Supported: dtype bf16 or f32; head_dim 64 or 128; 1 <= n_tree <= 128;
+ * n_q_heads a multiple of n_kv_heads; 0 <= prefix length <= max_prefix_len.
+ * Anything else returns LS_ERR_UNSUPPORTED.
+ */
+#ifndef LS_ATTN_H
+#define LS_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LS_OK = 0,
+    LS_ERR_NULL = -1,        /* a required pointer is NULL */
+    LS_ERR_SHAPE = -2,       /* a size is non-positive or inconsistent */
+    LS_ERR_DTYPE = -3,       /* dtype is not LS_BF16 / LS_F32 */
+    LS_ERR_STRIDE = -4,      /* a stride or pointer breaks the 16-byte row alignment */
+    LS_ERR_TREE = -5,        /* parents is not a topologically ordered forest */
+    LS_ERR_WORKSPACE = -6,   /* workspace missing, misaligned or too small */
+    LS_ERR_HIP = -7,         /* HIP reported a launch error */
+    LS_ERR_UNSUPPORTED = -8  /* valid request outside the supported set */
+} ls_status;
+
+typedef enum { LS_BF16 = 0, LS_F32 = 1 } ls_dtype;
+
+#define LS_MAX_TREE 128
+
+/* Problem descriptor (host memory, read during the call only). */
+typedef struct {
+    int32_t batch;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t n_tree;           /* tree tokens per sequence (the appendix's M) */
+    int32_t max_prefix_len;   /* host-known upper bound of every prefix length; sizes the grid */
+    int32_t dtype;            /* ls_dtype of q, k, v and out; lse is always float */
+    float   softmax_scale;    /* 0 selects 1/sqrt(head_dim) (the appendix's 1/sqrt(d_qk)) */
+    /* element strides of the (batch, head, row) axes; the head_dim axis has stride 1 */
+    int64_t q_stride[3];
+    int64_t o_stride[3];
+    int64_t kc_stride[3];
+    int64_t vc_stride[3];
+    int64_t kt_stride[3];
+    int64_t vt_stride[3];
+} ls_desc;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int ls_version(void);
+
+/* Static description of a status code; never NULL. */
+const char *ls_status_string(int status);
+
+/* Host-only check of the descriptor (shapes, dtype, strides, supported set). */
+int ls_validate_desc(const ls_desc *desc);
+
+/*
+ * Host-only check of a HOST copy of the parent arrays, [batch, n_tree] int32:
+ * parents[b][i] is -1 (a root; several roots are allowed) or in [0, i).
+ * Returns LS_OK or LS_ERR_TREE.
+ */
+int ls_validate_parents_host(const int32_t *parents, int32_t batch, int32_t n_tree);
+
+/*
+ * Number of key-axis splits the library would pick for the cached part of this
+ * problem (>= 1; depends only on the descriptor, so it is stable across calls).
+ */
+int ls_prefix_num_splits(const ls_desc *desc, int32_t *n_splits_out);
+
+/*
+ * Bytes of DEVICE workspace ls_hybrid_tree_attn needs for this descriptor:
+ * the tree mask, one error word per sequence, and (n_splits + 1) partial outputs and LSEs.
+ * The workspace must be 256-byte aligned.
+ */
+int ls_workspace_bytes(const ls_desc *desc, size_t *bytes_out);
+
+/*
+ * The whole path (Section 3.3): tree mask from `parents`, split-KV attention over the
+ * cache, masked attention over the tree tokens, log-sum-exp merge into out / lse.
+ *
+ *   prefix_lens  DEVICE int32[batch]; values are clamped into [0, max_prefix_len].
+ *                A sequence with prefix length 0 attends to its tree tokens only.
+ *   parents      DEVICE int32[batch, n_tree].  An entry outside {-1} u [0, i) is treated
+ *                as -1 and sets the sequence's error word in the workspace (see
+ *                ls_workspace_error); it never causes an out-of-bounds access.
+ *   out, lse     DEVICE, written in full.
+ *   workspace    DEVICE, >= ls_workspace_bytes(); contents are scratch.
+ */
+int ls_hybrid_tree_attn(const ls_desc *desc, const void *q,
+                        const void *k_cache, const void *v_cache, const int32_t *prefix_lens,
+                        const void *k_tree, const void *v_tree, const int32_t *parents,
+                        void *out, float *lse,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * DEVICE address, inside a workspace laid out for `desc`, of the int32[batch] error words
+ * that ls_hybrid_tree_attn writes: word b is 1 when sequence b had an invalid parents
+ * entry, else 0.  The caller may copy them back after synchronising.  Host-only pointer
+ * arithmetic.
+ */
+int ls_workspace_error(const ls_desc *desc, void *workspace, int32_t **err_word_out);
+
+/* ---- the four subsystems, callable on their own ------------------------------------ */
+
+/*
+ * (a) Tree mask (Section 2.1: masks derived from the prefix tree).  Row i gets bit j set
+ * iff j == i or j is an ancestor of i.
+ *   parents   DEVICE int32[batch, n_tree]
+ *   mask      DEVICE uint64[batch, n_tree, ceil(n_tree/64)]; bit j in word j/64, bit j%64
+ *   err_flag  DEVICE int32[batch], may be NULL; err_flag[b] is written on every call:
+ *             1 if sequence b had an entry outside {-1} u [0, i) (treated as -1), else 0
+ */
+int ls_build_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree,
+                       uint64_t *mask, int32_t *err_flag, void *stream);
+
+/*
+ * (b) Unmasked attention of every tree query over the cached keys, split along the key
+ * axis (appendix: o_cache and LSE_cache, per split).  Split s of a sequence covers cache
+ * rows [s*L, min((s+1)*L, prefix_len)), L = split length derived from max_prefix_len and
+ * n_splits (ls_prefix_split_len).  An empty split writes lse = -inf and leaves its output
+ * rows untouched.
+ *   n_splits  >= 1, or 0 for the library's choice (ls_prefix_num_splits)
+ *   o_part    DEVICE float[batch, n_q_heads, n_splits, n_tree, head_dim], normalised
+ *   lse_part  DEVICE float[batch, n_q_heads, n_splits, n_tree], natural log
+ */
+int ls_prefix_attn_splitkv(const ls_desc *desc, const void *q,
+                           const void *k_cache, const void *v_cache, const int32_t *prefix_lens,
+                           int32_t n_splits, float *o_part, float *lse_part, void *stream);
+
+/* Split length L (in cache rows) used for a given n_splits (0 = the library's choice). */
+int ls_prefix_split_len(const ls_desc *desc, int32_t n_splits, int32_t *split_len_out);
+
+/*
+ * (c) Masked attention of every tree query over the tree keys (appendix: o_specs and
+ * LSE_specs).  Key j is visible to row i iff bit j of mask row i is set; a row with an
+ * empty mask gets lse = -inf and zero output.
+ *   mask      DEVICE uint64[batch, n_tree, ceil(n_tree/64)]
+ *   o_tree    DEVICE float[batch, n_q_heads, n_tree, head_dim]
+ *   lse_tree  DEVICE float[batch, n_q_heads, n_tree]
+ */
+int ls_tree_attn_masked(const ls_desc *desc, const void *q,
+                        const void *k_tree, const void *v_tree, const uint64_t *mask,
+                        float *o_tree, float *lse_tree, void *stream);
+
+/*
+ * (d) Log-sum-exp merge of n_parts partial results per query row (Section 3.3
+ * "Aggregation", applied associatively).  Parts with lse = -inf are skipped, whatever
+ * their output rows hold; if every part is empty the row gets lse = -inf and zeros.
+ *   o_parts    DEVICE float[batch, n_q_heads, n_parts, n_tree, head_dim]
+ *   lse_parts  DEVICE float[batch, n_q_heads, n_parts, n_tree]
+ *   out        DEVICE dtype, strided by desc->o_stride;  lse DEVICE float[batch,n_q_heads,n_tree]
+ */
+int ls_lse_merge(const ls_desc *desc, int32_t n_parts,
+                 const float *o_parts, const float *lse_parts,
+                 void *out, float *lse, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LS_ATTN_H */

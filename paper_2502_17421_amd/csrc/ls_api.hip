@@ -1,0 +1,326 @@
+// Host side of the C ABI declared in include/ls_attn.h: argument checks, split planning,
+// workspace layout and kernel dispatch.  No device memory is allocated here.
+#include <cmath>
+#include <cstring>
+
+#include "ls_internal.hpp"
+
+namespace ls {
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+inline size_t elem_size(int dtype) { return dtype == LS_BF16 ? 2 : 4; }
+
+int check_stride(const int64_t s[3], int head_dim, size_t esz, bool is_output)
+{
+    for (int a = 0; a < 3; ++a) {
+        if (s[a] < 0) return LS_ERR_STRIDE;
+        if ((size_t)s[a] * esz % 16 != 0) return LS_ERR_STRIDE;
+    }
+    if (s[2] < head_dim) return LS_ERR_STRIDE;
+    if (is_output && (s[0] <= 0 || s[1] <= 0)) return LS_ERR_STRIDE;
+    return LS_OK;
+}
+
+int validate(const ls_desc *d)
+{
+    if (!d) return LS_ERR_NULL;
+    if (d->batch <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0 || d->n_tree <= 0 ||
+        d->max_prefix_len < 0)
+        return LS_ERR_SHAPE;
+    if (d->n_q_heads % d->n_kv_heads != 0) return LS_ERR_SHAPE;
+    if (d->dtype != LS_BF16 && d->dtype != LS_F32) return LS_ERR_DTYPE;
+    if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return LS_ERR_SHAPE;
+    if (d->head_dim != 64 && d->head_dim != 128) return LS_ERR_UNSUPPORTED;
+    if (d->n_tree > LS_MAX_TREE) return LS_ERR_UNSUPPORTED;
+    if ((int64_t)d->batch * d->n_kv_heads > 65535) return LS_ERR_UNSUPPORTED;
+    if ((int64_t)d->batch * d->n_q_heads * d->n_tree > (1 << 24)) return LS_ERR_UNSUPPORTED;
+    const size_t esz = elem_size(d->dtype);
+    int rc;
+    if ((rc = check_stride(d->q_stride, d->head_dim, esz, false))) return rc;
+    if ((rc = check_stride(d->o_stride, d->head_dim, esz, true))) return rc;
+    if ((rc = check_stride(d->kc_stride, d->head_dim, esz, false))) return rc;
+    if ((rc = check_stride(d->vc_stride, d->head_dim, esz, false))) return rc;
+    if ((rc = check_stride(d->kt_stride, d->head_dim, esz, false))) return rc;
+    if ((rc = check_stride(d->vt_stride, d->head_dim, esz, false))) return rc;
+    return LS_OK;
+}
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+Problem make_problem(const ls_desc &d, const void *q, const void *kc, const void *vc, const int32_t *plens,
+                     const void *kt, const void *vt)
+{
+    Problem p;
+    std::memset(&p, 0, sizeof(p));
+    p.q = q;
+    p.k_cache = kc;
+    p.v_cache = vc;
+    p.k_tree = kt;
+    p.v_tree = vt;
+    p.prefix_lens = plens;
+    p.batch = d.batch;
+    p.n_q_heads = d.n_q_heads;
+    p.n_kv_heads = d.n_kv_heads;
+    p.group = d.n_q_heads / d.n_kv_heads;
+    p.head_dim = d.head_dim;
+    p.n_tree = d.n_tree;
+    p.max_prefix_len = d.max_prefix_len;
+    const float scale = d.softmax_scale > 0.f ? d.softmax_scale : 1.0f / std::sqrt((float)d.head_dim);
+    p.scale_log2 = scale * kLog2e;
+    for (int a = 0; a < 3; ++a) {
+        p.q_stride[a] = d.q_stride[a];
+        p.kc_stride[a] = d.kc_stride[a];
+        p.vc_stride[a] = d.vc_stride[a];
+        p.kt_stride[a] = d.kt_stride[a];
+        p.vt_stride[a] = d.vt_stride[a];
+    }
+    return p;
+}
+
+int compute_units()
+{
+    static int cached = 0;
+    if (cached) return cached;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+        cached = n;
+    else {
+        (void)hipGetLastError();
+        return 256;  // MI355X; not cached so a later call with a device present asks again
+    }
+    return cached;
+}
+
+struct Workspace {
+    size_t off_mask, off_err, off_lse, off_o, total;
+    int32_t n_parts;
+};
+
+Workspace layout(const ls_desc &d, const SplitPlan &plan)
+{
+    Workspace w;
+    const size_t words = (d.n_tree + 63) / 64;
+    w.n_parts = plan.n_splits + 1;
+    const size_t rows = (size_t)d.batch * d.n_q_heads * w.n_parts * d.n_tree;
+    w.off_mask = 0;
+    w.off_err = align_up(w.off_mask + (size_t)d.batch * d.n_tree * words * sizeof(uint64_t));
+    w.off_lse = align_up(w.off_err + (size_t)d.batch * sizeof(int32_t));
+    w.off_o = align_up(w.off_lse + rows * sizeof(float));
+    w.total = align_up(w.off_o + rows * d.head_dim * sizeof(float));
+    return w;
+}
+
+}  // namespace
+
+// Split schedule.  The cached keys of every sequence are cut into pieces of split_len rows
+// (a multiple of 64, the MFMA kernel's key tile); the grid is sized for max_prefix_len.
+// Left to the library, the count aims at about one workgroup per compute unit.
+SplitPlan plan_splits(const ls_desc &d, int32_t request)
+{
+    constexpr int kTile = 64;
+    SplitPlan plan;
+    const int64_t max_p = d.max_prefix_len;
+    int64_t s = request;
+    if (s <= 0) {
+        const int group = d.n_q_heads / d.n_kv_heads;
+        const int rows_kv = group * d.n_tree;
+        const int rows_wg = d.dtype == LS_BF16 ? 256 : 32;
+        const int64_t units = (int64_t)d.batch * d.n_kv_heads * ((rows_kv + rows_wg - 1) / rows_wg);
+        const int cus = compute_units();
+        s = (cus + units - 1) / units;
+        if (s < 1) s = 1;
+    }
+    int64_t len = (max_p + s - 1) / s;
+    len = (len + kTile - 1) / kTile * kTile;
+    if (len < kTile) len = kTile;
+    if (request <= 0) {
+        s = (max_p + len - 1) / len;
+        if (s < 1) s = 1;
+    }
+    plan.n_splits = (int32_t)s;
+    plan.split_len = (int32_t)len;
+    return plan;
+}
+
+}  // namespace ls
+
+using namespace ls;
+
+extern "C" {
+
+int ls_version(void) { return 100; }
+
+const char *ls_status_string(int status)
+{
+    switch (status) {
+    case LS_OK: return "ok";
+    case LS_ERR_NULL: return "a required pointer is NULL";
+    case LS_ERR_SHAPE: return "a size is non-positive or inconsistent";
+    case LS_ERR_DTYPE: return "unknown dtype";
+    case LS_ERR_STRIDE: return "stride or pointer breaks the 16-byte row alignment";
+    case LS_ERR_TREE: return "parents is not a topologically ordered forest";
+    case LS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LS_ERR_HIP: return "HIP reported a launch error";
+    case LS_ERR_UNSUPPORTED: return "request outside the supported set";
+    default: return "unknown status";
+    }
+}
+
+int ls_validate_desc(const ls_desc *desc) { return validate(desc); }
+
+int ls_validate_parents_host(const int32_t *parents, int32_t batch, int32_t n_tree)
+{
+    if (!parents) return LS_ERR_NULL;
+    if (batch <= 0 || n_tree <= 0) return LS_ERR_SHAPE;
+    for (int32_t b = 0; b < batch; ++b)
+        for (int32_t i = 0; i < n_tree; ++i) {
+            const int32_t p = parents[(size_t)b * n_tree + i];
+            if (p < -1 || p >= i) return LS_ERR_TREE;
+        }
+    return LS_OK;
+}
+
+int ls_prefix_num_splits(const ls_desc *desc, int32_t *n_splits_out)
+{
+    if (!n_splits_out) return LS_ERR_NULL;
+    const int rc = validate(desc);
+    if (rc) return rc;
+    *n_splits_out = plan_splits(*desc, 0).n_splits;
+    return LS_OK;
+}
+
+int ls_prefix_split_len(const ls_desc *desc, int32_t n_splits, int32_t *split_len_out)
+{
+    if (!split_len_out) return LS_ERR_NULL;
+    const int rc = validate(desc);
+    if (rc) return rc;
+    if (n_splits < 0) return LS_ERR_SHAPE;
+    *split_len_out = plan_splits(*desc, n_splits).split_len;
+    return LS_OK;
+}
+
+int ls_workspace_bytes(const ls_desc *desc, size_t *bytes_out)
+{
+    if (!bytes_out) return LS_ERR_NULL;
+    const int rc = validate(desc);
+    if (rc) return rc;
+    *bytes_out = layout(*desc, plan_splits(*desc, 0)).total;
+    return LS_OK;
+}
+
+int ls_workspace_error(const ls_desc *desc, void *workspace, int32_t **err_out)
+{
+    if (!workspace || !err_out) return LS_ERR_NULL;
+    const int rc = validate(desc);
+    if (rc) return rc;
+    *err_out = (int32_t *)((char *)workspace + layout(*desc, plan_splits(*desc, 0)).off_err);
+    return LS_OK;
+}
+
+int ls_build_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree, uint64_t *mask,
+                       int32_t *err_flag, void *stream)
+{
+    if (!parents || !mask) return LS_ERR_NULL;
+    if (batch <= 0 || n_tree <= 0) return LS_ERR_SHAPE;
+    if (n_tree > LS_MAX_TREE || batch > 65535) return LS_ERR_UNSUPPORTED;
+    return launch_tree_mask(parents, batch, n_tree, mask, err_flag, (hipStream_t)stream) == hipSuccess
+               ? LS_OK
+               : LS_ERR_HIP;
+}
+
+int ls_prefix_attn_splitkv(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *prefix_lens, int32_t n_splits, float *o_part, float *lse_part,
+                           void *stream)
+{
+    const int rc = validate(desc);
+    if (rc) return rc;
+    if (!q || !prefix_lens || !o_part || !lse_part) return LS_ERR_NULL;
+    if (desc->max_prefix_len > 0 && (!k_cache || !v_cache)) return LS_ERR_NULL;
+    if (n_splits < 0 || n_splits > 65535) return LS_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o_part)) return LS_ERR_STRIDE;
+    const SplitPlan plan = plan_splits(*desc, n_splits);
+    const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, nullptr, nullptr);
+    const Partials out{o_part, lse_part, plan.n_splits, 0};
+    hipError_t e;
+    if (prefix_mfma_supports(p, desc->dtype))
+        e = launch_prefix_mfma(p, plan, out, (hipStream_t)stream);
+    else
+        e = launch_prefix_valu(p, desc->dtype, plan, out, (hipStream_t)stream);
+    return e == hipSuccess ? LS_OK : LS_ERR_HIP;
+}
+
+int ls_tree_attn_masked(const ls_desc *desc, const void *q, const void *k_tree, const void *v_tree,
+                        const uint64_t *mask, float *o_tree, float *lse_tree, void *stream)
+{
+    const int rc = validate(desc);
+    if (rc) return rc;
+    if (!q || !k_tree || !v_tree || !mask || !o_tree || !lse_tree) return LS_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_tree) || !aligned16(v_tree) || !aligned16(o_tree)) return LS_ERR_STRIDE;
+    const Problem p = make_problem(*desc, q, nullptr, nullptr, nullptr, k_tree, v_tree);
+    const Partials out{o_tree, lse_tree, 1, 0};
+    return launch_tree_attn(p, desc->dtype, mask, out, (hipStream_t)stream) == hipSuccess ? LS_OK : LS_ERR_HIP;
+}
+
+int ls_lse_merge(const ls_desc *desc, int32_t n_parts, const float *o_parts, const float *lse_parts, void *out,
+                 float *lse, void *stream)
+{
+    const int rc = validate(desc);
+    if (rc) return rc;
+    if (!o_parts || !lse_parts || !out || !lse) return LS_ERR_NULL;
+    if (n_parts <= 0) return LS_ERR_SHAPE;
+    if (!aligned16(o_parts) || !aligned16(out)) return LS_ERR_STRIDE;
+    return launch_merge(desc->batch, desc->n_q_heads, desc->n_tree, desc->head_dim, desc->dtype, n_parts,
+                        o_parts, lse_parts, out, desc->o_stride, lse, (hipStream_t)stream) == hipSuccess
+               ? LS_OK
+               : LS_ERR_HIP;
+}
+
+int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                        const int32_t *prefix_lens, const void *k_tree, const void *v_tree,
+                        const int32_t *parents, void *out, float *lse, void *workspace, size_t workspace_bytes,
+                        void *stream)
+{
+    const int rc = validate(desc);
+    if (rc) return rc;
+    if (!q || !prefix_lens || !k_tree || !v_tree || !parents || !out || !lse) return LS_ERR_NULL;
+    if (desc->max_prefix_len > 0 && (!k_cache || !v_cache)) return LS_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_tree) || !aligned16(v_tree) ||
+        !aligned16(out))
+        return LS_ERR_STRIDE;
+    const SplitPlan plan = plan_splits(*desc, 0);
+    const Workspace w = layout(*desc, plan);
+    if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < w.total) return LS_ERR_WORKSPACE;
+
+    char *base = (char *)workspace;
+    uint64_t *mask = (uint64_t *)(base + w.off_mask);
+    int32_t *err = (int32_t *)(base + w.off_err);
+    float *lse_parts = (float *)(base + w.off_lse);
+    float *o_parts = (float *)(base + w.off_o);
+    hipStream_t s = (hipStream_t)stream;
+    const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree);
+
+    // (b) cached keys -> parts [0, n_splits)
+    const Partials cache_out{o_parts, lse_parts, w.n_parts, 0};
+    hipError_t e;
+    if (prefix_mfma_supports(p, desc->dtype))
+        e = launch_prefix_mfma(p, plan, cache_out, s);
+    else
+        e = launch_prefix_valu(p, desc->dtype, plan, cache_out, s);
+    if (e != hipSuccess) return LS_ERR_HIP;
+    // (a) tree mask, (c) tree keys -> part n_splits
+    if (launch_tree_mask(parents, desc->batch, desc->n_tree, mask, err, s) != hipSuccess) return LS_ERR_HIP;
+    const Partials tree_out{o_parts, lse_parts, w.n_parts, plan.n_splits};
+    if (launch_tree_attn(p, desc->dtype, mask, tree_out, s) != hipSuccess) return LS_ERR_HIP;
+    // (d) merge
+    if (launch_merge(desc->batch, desc->n_q_heads, desc->n_tree, desc->head_dim, desc->dtype, w.n_parts, o_parts,
+                     lse_parts, out, desc->o_stride, lse, s) != hipSuccess)
+        return LS_ERR_HIP;
+    return LS_OK;
+}
+
+}  // extern "C"

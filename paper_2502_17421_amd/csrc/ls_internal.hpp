@@ -1,0 +1,86 @@
+// Internal declarations shared by the host API and the kernel translation units.
+// Nothing here is part of the C ABI (see include/ls_attn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ls_attn.h"
+
+namespace ls {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Everything a kernel needs to find its operands; passed by value.
+struct Problem {
+    const void *q;
+    const void *k_cache;
+    const void *v_cache;
+    const void *k_tree;
+    const void *v_tree;
+    const int32_t *prefix_lens;
+    int32_t batch, n_q_heads, n_kv_heads, group, head_dim, n_tree, max_prefix_len;
+    float scale_log2;  // softmax scale times log2(e): logits are kept in base 2 inside kernels
+    int64_t q_stride[3], kc_stride[3], vc_stride[3], kt_stride[3], vt_stride[3];
+};
+
+// Where partial results go: o [batch, n_q_heads, parts_stride, n_tree, head_dim] float,
+// lse [batch, n_q_heads, parts_stride, n_tree] float.  A producer writes parts
+// [part_base, part_base + its own count).
+struct Partials {
+    float *o;
+    float *lse;
+    int32_t parts_stride;
+    int32_t part_base;
+};
+
+struct SplitPlan {
+    int32_t n_splits;   // parts the cached-key kernel writes
+    int32_t split_len;  // cache rows per split
+};
+
+// bf16 <-> float on raw 16-bit patterns (round to nearest even, NaN kept quiet).
+__device__ __forceinline__ float bf16_to_float(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float *p) { return *p; }
+    static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {
+    static __device__ __forceinline__ float load(const uint16_t *p) { return bf16_to_float(*p); }
+    static __device__ __forceinline__ void store(uint16_t *p, float v) { *p = float_to_bf16(v); }
+};
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Host launchers, one per kernel family.  Each returns a hipError_t from the launch.
+hipError_t launch_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree, uint64_t *mask,
+                            int32_t *err_flag, hipStream_t stream);
+hipError_t launch_tree_attn(const Problem &p, int dtype, const uint64_t *mask, const Partials &out,
+                            hipStream_t stream);
+hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
+                              hipStream_t stream);
+hipError_t launch_prefix_mfma(const Problem &p, const SplitPlan &plan, const Partials &out,
+                              hipStream_t stream);
+bool prefix_mfma_supports(const Problem &p, int dtype);
+SplitPlan plan_splits(const ls_desc &d, int32_t n_splits_request);
+hipError_t launch_merge(int32_t batch, int32_t n_q_heads, int32_t n_tree, int32_t head_dim, int dtype,
+                        int32_t n_parts, const float *o_parts, const float *lse_parts, void *out,
+                        const int64_t o_stride[3], float *lse, hipStream_t stream);
+
+}  // namespace ls

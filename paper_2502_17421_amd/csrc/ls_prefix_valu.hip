@@ -1,0 +1,153 @@
+// Split-KV attention over the cached keys on the vector ALUs, with float arithmetic
+// throughout.  This is the true-fp32 variant of step (b) (appendix: o_cache, LSE_cache per
+// split) and the fallback for shapes the MFMA kernel does not take.
+//
+// One workgroup = one (sequence, KV head, block of 32 query rows, key split).  The query
+// rows of a KV head are the G*T rows (g, t) of its G query heads.  Keys are streamed in
+// tiles of 32 through LDS; scores, the online softmax and the P*V product are computed per
+// tile.  Thread (r, c) = (tid / 8, tid % 8) owns query row r: it computes the scores of
+// keys c, c+8, c+16, c+24 of the tile and accumulates output columns c, c+8, ...
+#include "ls_internal.hpp"
+
+namespace ls {
+
+namespace {
+constexpr int TQ = 32;  // query rows per workgroup
+constexpr int TK = 32;  // keys per tile
+}
+
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
+{
+    constexpr int KP = D + 1;  // padded key row: threads c = 0..7 hit distinct banks
+    __shared__ float q_s[TQ][D];
+    __shared__ float k_s[TK][KP];
+    __shared__ float v_s[TK][D];
+    __shared__ float p_s[TQ][TK + 1];
+
+    const int tid = threadIdx.x;
+    const int r = tid >> 3, c = tid & 7;
+    const int split = blockIdx.x;
+    const int qblock = blockIdx.y;
+    const int b = blockIdx.z / p.n_kv_heads;
+    const int g = blockIdx.z % p.n_kv_heads;
+    const int rows_kv = p.group * p.n_tree;  // query rows that share this KV head
+
+    int plen = p.prefix_lens[b];
+    plen = plen < 0 ? 0 : (plen > p.max_prefix_len ? p.max_prefix_len : plen);
+    const int k_lo = split * plan.split_len;
+    int k_hi = k_lo + plan.split_len;
+    k_hi = k_hi > plen ? plen : k_hi;
+
+    // my query row
+    const int m = qblock * TQ + r;
+    const bool row_ok = m < rows_kv;
+    const int hq = g * p.group + (row_ok ? m / p.n_tree : 0);
+    const int ti = row_ok ? m % p.n_tree : 0;
+
+    // stage the query block, pre-multiplied by scale*log2(e)
+    for (int e = tid; e < TQ * D; e += 256) {
+        const int rr = e / D, dd = e % D;
+        const int mm = qblock * TQ + rr;
+        float v = 0.f;
+        if (mm < rows_kv) {
+            const T *qp = (const T *)p.q + b * p.q_stride[0] + (g * p.group + mm / p.n_tree) * p.q_stride[1] +
+                          (mm % p.n_tree) * p.q_stride[2];
+            v = Elem<T>::load(qp + dd) * p.scale_log2;
+        }
+        q_s[rr][dd] = v;
+    }
+
+    float acc[D / 8];
+#pragma unroll
+    for (int k = 0; k < D / 8; ++k) acc[k] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const T *kbase = (const T *)p.k_cache + b * p.kc_stride[0] + g * p.kc_stride[1];
+    const T *vbase = (const T *)p.v_cache + b * p.vc_stride[0] + g * p.vc_stride[1];
+
+    for (int k0 = k_lo; k0 < k_hi; k0 += TK) {
+        __syncthreads();  // previous tile fully consumed (and q_s visible on the first pass)
+        for (int e = tid; e < TK * D; e += 256) {
+            const int jj = e / D, dd = e % D;
+            const int key = k0 + jj;
+            float kv = 0.f, vv = 0.f;
+            if (key < k_hi) {
+                kv = Elem<T>::load(kbase + key * p.kc_stride[2] + dd);
+                vv = Elem<T>::load(vbase + key * p.vc_stride[2] + dd);
+            }
+            k_s[jj][dd] = kv;
+            v_s[jj][dd] = vv;
+        }
+        __syncthreads();
+
+        float s[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) s[a] = 0.f;
+        for (int dd = 0; dd < D; ++dd) {
+            const float qd = q_s[r][dd];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) s[a] += qd * k_s[c + 8 * a][dd];
+        }
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            if (k0 + c + 8 * a >= k_hi) s[a] = -INFINITY;
+            tmax = fmaxf(tmax, s[a]);
+        }
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) tmax = fmaxf(tmax, __shfl_xor(tmax, off, kWave));
+        const float m_new = fmaxf(m_run, tmax);  // finite: every tile holds at least one key
+        const float alpha = exp2f(m_run - m_new);
+        float psum = 0.f;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const float pj = exp2f(s[a] - m_new);
+            p_s[r][c + 8 * a] = pj;
+            psum += pj;
+        }
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) psum += __shfl_xor(psum, off, kWave);
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int k = 0; k < D / 8; ++k) acc[k] *= alpha;
+        __syncthreads();  // p_s row r complete
+        for (int jj = 0; jj < TK; ++jj) {
+            const float pj = p_s[r][jj];
+#pragma unroll
+            for (int k = 0; k < D / 8; ++k) acc[k] += pj * v_s[jj][c + 8 * k];
+        }
+    }
+
+    if (!row_ok) return;
+    const size_t prow =
+        (((size_t)b * p.n_q_heads + hq) * out.parts_stride + out.part_base + split) * p.n_tree + ti;
+    if (l_run > 0.f) {
+        const float inv = 1.f / l_run;
+        float *orow = out.o + prow * D;
+#pragma unroll
+        for (int k = 0; k < D / 8; ++k) orow[c + 8 * k] = acc[k] * inv;
+        if (c == 0) out.lse[prow] = (m_run + log2f(l_run)) * kLn2;
+    } else if (c == 0) {
+        out.lse[prow] = -INFINITY;
+    }
+}
+
+hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
+                              hipStream_t stream)
+{
+    const int rows_kv = p.group * p.n_tree;
+    const dim3 block(256), grid(plan.n_splits, (rows_kv + TQ - 1) / TQ, p.batch * p.n_kv_heads);
+#define LS_PV_CASE(T, DD) hipLaunchKernelGGL((prefix_valu_kernel<T, DD>), grid, block, 0, stream, p, plan, out)
+    if (dtype == LS_BF16 && p.head_dim == 128) LS_PV_CASE(uint16_t, 128);
+    else if (dtype == LS_BF16 && p.head_dim == 64) LS_PV_CASE(uint16_t, 64);
+    else if (dtype == LS_F32 && p.head_dim == 128) LS_PV_CASE(float, 128);
+    else if (dtype == LS_F32 && p.head_dim == 64) LS_PV_CASE(float, 64);
+    else return hipErrorInvalidValue;
+#undef LS_PV_CASE
+    return hipGetLastError();
+}
+
+}  // namespace ls

@@ -1,0 +1,180 @@
+"""CPU-side tests of the C-ABI library: it loads, exports every function the header
+declares, the descriptor struct matches between C and the binding, and argument errors
+come back as status codes before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ls_attn.h")
+
+from paper_2502_17421_amd import binding as ls
+from paper_2502_17421_amd import build as ls_build
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built_library():
+    if not os.path.exists(ls.LIB_PATH):
+        ls_build.build_library()
+    return ls.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ls_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(built_library):
+    names = declared_functions()
+    assert "ls_hybrid_tree_attn" in names and len(names) >= 12
+    for n in names:
+        assert hasattr(built_library, n), f"{n} declared in ls_attn.h but not exported"
+    # and the binding offers a function of the same name for each
+    for n in names:
+        assert callable(getattr(ls, n)), f"binding lacks {n}"
+
+
+def test_descriptor_layout_matches_c(tmp_path):
+    src = tmp_path / "layout.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "ls_attn.h"\n'
+        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu\\n\", sizeof(ls_desc), offsetof(ls_desc, softmax_scale),"
+        " offsetof(ls_desc, q_stride), offsetof(ls_desc, o_stride), offsetof(ls_desc, kc_stride),"
+        " offsetof(ls_desc, vt_stride)); return 0;}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o",
+                    str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    d = ls.ls_desc
+    assert got == [ctypes.sizeof(d), d.softmax_scale.offset, d.q_stride.offset, d.o_stride.offset,
+                   d.kc_stride.offset, d.vt_stride.offset]
+
+
+def test_version_and_status_strings():
+    assert ls.ls_version() >= 100
+    seen = set()
+    for code in range(0, -9, -1):
+        s = ls.ls_status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 9
+    assert ls.ls_status_string(-99) == "unknown status"
+
+
+def good_desc(dtype=ls.LS_BF16, b=1, hq=8, hkv=2, d=128, t=16, p=1000):
+    x = ls.ls_desc()
+    x.batch, x.n_q_heads, x.n_kv_heads, x.head_dim, x.n_tree, x.max_prefix_len = b, hq, hkv, d, t, p
+    x.dtype = dtype
+    x.softmax_scale = 0.0
+    for name, h, l in (("q_stride", hq, t), ("o_stride", hq, t), ("kc_stride", hkv, max(p, 1)),
+                       ("vc_stride", hkv, max(p, 1)), ("kt_stride", hkv, t), ("vt_stride", hkv, t)):
+        f = getattr(x, name)
+        f[0], f[1], f[2] = h * l * d, l * d, d
+    return x
+
+
+def test_validate_desc_codes():
+    assert ls.ls_validate_desc(good_desc()) == ls.LS_OK
+    assert ls.ls_validate_desc(good_desc(dtype=ls.LS_F32, d=64)) == ls.LS_OK
+    x = good_desc(); x.batch = 0
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_SHAPE
+    x = good_desc(); x.n_kv_heads = 3
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_SHAPE
+    x = good_desc(); x.max_prefix_len = -1
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_SHAPE
+    x = good_desc(); x.softmax_scale = float("nan")
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_SHAPE
+    x = good_desc(); x.dtype = 7
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_DTYPE
+    x = good_desc(); x.head_dim = 96
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_UNSUPPORTED
+    x = good_desc(); x.n_tree = 129
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_UNSUPPORTED
+    x = good_desc(); x.kc_stride[2] = 132          # 264-byte rows: not 16-byte aligned
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_STRIDE
+    x = good_desc(); x.q_stride[2] = 64            # rows overlap
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_STRIDE
+    x = good_desc(); x.o_stride[1] = 0
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_STRIDE
+    x = good_desc(); x.vt_stride[0] = -128
+    assert ls.ls_validate_desc(x) == ls.LS_ERR_STRIDE
+    assert ls.lib().ls_validate_desc(None) == ls.LS_ERR_NULL
+
+
+def test_validate_parents_host():
+    ok = torch.tensor([[-1, 0, 0, 2], [-1, -1, 1, 2]], dtype=torch.int32)
+    assert ls.ls_validate_parents_host(ok) == ls.LS_OK
+    for bad in ([[0, 0]], [[-1, 1]], [[-1, -2]], [[-1, 0, 2]]):
+        assert ls.ls_validate_parents_host(torch.tensor(bad, dtype=torch.int32)) == ls.LS_ERR_TREE
+    assert ls.lib().ls_validate_parents_host(None, 1, 1) == ls.LS_ERR_NULL
+
+
+def test_split_plan_and_workspace_are_stable_and_sane():
+    d = good_desc(hq=32, hkv=8, t=64, p=32768)
+    s = ls.ls_prefix_num_splits(d)
+    assert s == ls.ls_prefix_num_splits(d) and 1 <= s <= 32768 // 64
+    length = ls.ls_prefix_split_len(d, 0)
+    assert length % 64 == 0 and (s - 1) * length < 32768 <= s * length
+    assert ls.ls_prefix_split_len(d, 5) % 64 == 0 and ls.ls_prefix_split_len(d, 5) * 5 >= 32768
+    n = ls.ls_workspace_bytes(d)
+    parts = (s + 1) * 32 * 64
+    assert n >= parts * 128 * 4 + parts * 4 + 64 * 8 and n % 256 == 0
+    z = good_desc(p=0)
+    assert ls.ls_prefix_num_splits(z) >= 1 and ls.ls_workspace_bytes(z) > 0
+    bad = good_desc(); bad.head_dim = 80
+    with pytest.raises(ls.LsError):
+        ls.ls_workspace_bytes(bad)
+
+
+def test_device_entry_points_reject_bad_arguments_on_the_host():
+    """Null pointers, bad descriptors and a short workspace come back as codes; nothing is
+    launched, so this runs without a GPU (stream handle 0)."""
+    d = good_desc()
+    L = ls.lib()
+    one = ctypes.c_void_p(256)     # a non-null, aligned stand-in that is never dereferenced
+    odd = ctypes.c_void_p(260)
+    dp = ctypes.byref(d)
+    assert L.ls_hybrid_tree_attn(dp, None, one, one, one, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_NULL
+    assert L.ls_hybrid_tree_attn(dp, one, None, one, one, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_NULL
+    assert L.ls_hybrid_tree_attn(dp, odd, one, one, one, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_STRIDE
+    assert L.ls_hybrid_tree_attn(dp, one, one, one, one, one, one, one, one, one, None, 0, None) == ls.LS_ERR_WORKSPACE
+    assert L.ls_hybrid_tree_attn(dp, one, one, one, one, one, one, one, one, one, one, 16, None) == ls.LS_ERR_WORKSPACE
+    assert L.ls_hybrid_tree_attn(dp, one, one, one, one, one, one, one, one, one, odd, 1 << 40, None) == ls.LS_ERR_WORKSPACE
+    bad = good_desc(); bad.n_tree = 0
+    assert L.ls_hybrid_tree_attn(ctypes.byref(bad), one, one, one, one, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_SHAPE
+    assert L.ls_build_tree_mask(None, 1, 4, one, None, None) == ls.LS_ERR_NULL
+    assert L.ls_build_tree_mask(one, 1, 0, one, None, None) == ls.LS_ERR_SHAPE
+    assert L.ls_build_tree_mask(one, 1, 129, one, None, None) == ls.LS_ERR_UNSUPPORTED
+    assert L.ls_prefix_attn_splitkv(dp, one, one, one, None, 0, one, one, None) == ls.LS_ERR_NULL
+    assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, -1, one, one, None) == ls.LS_ERR_SHAPE
+    assert L.ls_tree_attn_masked(dp, one, one, one, None, one, one, None) == ls.LS_ERR_NULL
+    assert L.ls_lse_merge(dp, 0, one, one, one, one, None) == ls.LS_ERR_SHAPE
+    assert L.ls_lse_merge(dp, 2, one, one, None, one, None) == ls.LS_ERR_NULL
+
+
+def test_binding_raises_when_library_is_missing(tmp_path, monkeypatch):
+    """No silent fallback: without the built library the binding refuses to work."""
+    monkeypatch.setattr(ls, "_lib", None)
+    monkeypatch.setattr(ls, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        ls.lib()
+
+
+def test_product_code_does_not_touch_the_oracle():
+    """The package and its sources never import or mention the oracle package."""
+    pkg = os.path.join(ROOT, "paper_2502_17421_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), f
+                assert "ls_oracle" not in text, f
+    for f in ("ls_oracle.c", "__init__.py"):
+        text = open(os.path.join(ROOT, "oracle", f)).read()
+        assert "paper_2502_17421_amd" not in text and "ls_attn.h" not in text

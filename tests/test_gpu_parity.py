@@ -1,0 +1,337 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI, on a real MI355X.
+
+Small cases are compared element by element (sizes the oracle finishes in seconds that still
+span several key tiles, several splits and ragged tails).  The five benchmark shapes are
+run at full size in the configuration the benchmark times (library-chosen splits) and
+compared on sampled query rows, which the oracle computes one by one.
+"""
+import dataclasses
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_17421_amd import binding as ls
+from paper_2502_17421_amd import synth
+from util import DeviceBatch, gates, oracle_full, to_dev, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def device():
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    ls.lib()
+    return torch.device("cuda")
+
+
+def small(name, prefix, variant="iid", **over):
+    w = dataclasses.replace(synth.WORKLOADS[name], **over) if over else synth.WORKLOADS[name]
+    return synth.make_batch(w, variant, prefix_override=prefix)
+
+
+# ------------------------------------------------------------------------- (a) mask ----
+
+@pytest.mark.parametrize("n_tree", [1, 2, 5, 63, 64, 65, 100, 128])
+def test_mask_bit_exact(n_tree):
+    rng = np.random.default_rng(500 + n_tree)
+    trees = [synth.tree_uniform(rng, n_tree), synth.tree_chain(n_tree), synth.tree_star(n_tree),
+             synth.tree_constrained(rng, n_tree, 10, 4) if n_tree <= 128 else synth.tree_chain(n_tree)]
+    forest = synth.tree_uniform(rng, n_tree)
+    forest[rng.integers(0, n_tree, size=3)] = -1
+    trees.append(forest)
+    parents = torch.from_numpy(np.stack(trees)).cuda()
+    words = (n_tree + 63) // 64
+    mask = torch.full((len(trees), n_tree, words), -1, dtype=torch.int64, device="cuda")
+    err = torch.full((len(trees),), 7, dtype=torch.int32, device="cuda")
+    ls.ls_build_tree_mask(parents, mask, err)
+    torch.cuda.synchronize()
+    got = mask.cpu().numpy().view(np.uint64)
+    for b, tr in enumerate(trees):
+        np.testing.assert_array_equal(got[b], oracle.tree_mask(tr))
+    assert err.cpu().tolist() == [0] * len(trees)
+
+
+def test_mask_invalid_entries_are_flagged_and_cut():
+    good = np.asarray([-1, 0, 1, 1, 3, 4], dtype=np.int32)
+    bad1 = np.asarray([-1, 0, 5, 1, 3, 2], dtype=np.int32)   # entry 2 points forward
+    bad2 = np.asarray([-1, 0, 1, -9, 3, 4], dtype=np.int32)  # entry 3 below -1
+    parents = torch.from_numpy(np.stack([good, bad1, bad2])).cuda()
+    mask = torch.zeros((3, 6, 1), dtype=torch.int64, device="cuda")
+    err = torch.zeros((3,), dtype=torch.int32, device="cuda")
+    ls.ls_build_tree_mask(parents, mask, err)
+    torch.cuda.synchronize()
+    assert err.cpu().tolist() == [0, 1, 1]
+    got = mask.cpu().numpy().view(np.uint64)
+    cut1, cut2 = bad1.copy(), bad2.copy()
+    cut1[2] = -1
+    cut2[3] = -1
+    np.testing.assert_array_equal(got[0], oracle.tree_mask(good))
+    np.testing.assert_array_equal(got[1], oracle.tree_mask(cut1))
+    np.testing.assert_array_equal(got[2], oracle.tree_mask(cut2))
+
+
+# ------------------------------------------------------------------ (c) tree attention ----
+
+@pytest.mark.parametrize("dtype,d,t,hq,hkv", [("f32", 64, 16, 4, 1), ("f32", 128, 37, 6, 2),
+                                              ("bf16", 128, 64, 32, 8), ("bf16", 64, 128, 10, 2),
+                                              ("bf16", 128, 1, 4, 4)])
+def test_tree_attention_alone(dtype, d, t, hq, hkv):
+    rng = np.random.default_rng(600 + t)
+    seqs = []
+    for b in range(2):
+        parents = synth.tree_constrained(rng, t, 10, 4) if b == 0 else synth.tree_uniform(rng, t)
+        seqs.append(synth.make_sequence(rng, dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n_tree=t,
+                                        prefix_len=1, parents=parents, variant="peaked"))
+    dt = torch_dtype(dtype)
+    q = torch.stack([to_dev(s.q, dt) for s in seqs])
+    kt = torch.stack([to_dev(s.k_tree, dt) for s in seqs])
+    vt = torch.stack([to_dev(s.v_tree, dt) for s in seqs])
+    mask = torch.from_numpy(np.stack([oracle.tree_mask(s.parents) for s in seqs]).view(np.int64)).cuda()
+    o = torch.full((2, hq, t, d), float("nan"), dtype=torch.float32, device="cuda")
+    l = torch.full((2, hq, t), float("nan"), dtype=torch.float32, device="cuda")
+    desc = ls.make_desc(q, None, None, kt, vt, None, 0)
+    ls.ls_tree_attn_masked(desc, q, kt, vt, mask, o, l)
+    torch.cuda.synchronize()
+    for b, s in enumerate(seqs):
+        ro, rl = oracle.attn_all(s.q, s.k_cache, s.v_cache, s.k_tree, s.v_tree, s.parents,
+                                 prefix_lo=0, prefix_hi=0, use_tree=True)
+        # partial results are float on both dtypes: only the inputs are rounded
+        say(gates(o[b].cpu().numpy(), l[b].cpu().numpy(), ro, rl, "f32" if dtype == "f32" else "bf16",
+                  f"tree-only {dtype} b={b}"))
+        assert np.abs(o[b].cpu().numpy() - ro).max() < 2e-5
+
+
+# --------------------------------------------------------------------------- (d) merge ----
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("f32", 128), ("bf16", 64)])
+def test_merge_alone(dtype, d):
+    rng = np.random.default_rng(700 + d)
+    b, hq, t, parts = 2, 3, 9, 5
+    o_parts = rng.standard_normal((b, hq, parts, t, d)).astype(np.float32)
+    lse_parts = (rng.standard_normal((b, hq, parts, t)) * 4).astype(np.float32)
+    lse_parts[0, 0, 1, :] = -np.inf          # an empty part whose output rows hold NaN
+    o_parts[0, 0, 1] = np.nan
+    lse_parts[1, 2, :, 4] = -np.inf          # a row with every part empty
+    dt = torch_dtype(dtype)
+    out = torch.full((b, hq, t, d), float("nan"), dtype=dt, device="cuda")
+    lse = torch.full((b, hq, t), float("nan"), dtype=torch.float32, device="cuda")
+    desc = ls.make_desc(out, None, None, None, None, out, 0)
+    desc.n_kv_heads = hq
+    ls.ls_lse_merge(desc, parts, torch.from_numpy(o_parts).cuda(), torch.from_numpy(lse_parts).cuda(), out, lse)
+    torch.cuda.synchronize()
+    ro, rl = oracle.lse_merge(np.moveaxis(o_parts, 2, 3).reshape(-1, parts, d).astype(np.float64),
+                              np.moveaxis(lse_parts, 2, 3).reshape(-1, parts).astype(np.float64))
+    got_o = out.float().cpu().numpy().reshape(-1, d)
+    got_l = lse.cpu().numpy().reshape(-1)
+    dead = np.isneginf(rl)
+    assert dead.sum() == 1 and np.all(np.isneginf(got_l[dead])) and np.all(got_o[dead] == 0)
+    tol = 1e-5 if dtype == "f32" else 2e-2
+    assert np.abs(got_o[~dead] - ro[~dead]).max() <= tol
+    assert np.abs(got_l[~dead] - rl[~dead]).max() <= 1e-5
+
+
+# ------------------------------------------------------------- (b) cached keys, by split ----
+
+PREFIX_CASES = [
+    # dtype, hq, hkv, d, t, prefix lengths, n_splits
+    ("f32", 4, 1, 64, 16, [1024], 0),
+    ("f32", 6, 2, 128, 11, [333, 70], 3),
+    ("bf16", 32, 8, 128, 64, [1500], 0),       # 256-row query tile, ragged last key tile
+    ("bf16", 32, 8, 128, 64, [64 * 7], 7),     # whole tiles only
+    ("bf16", 8, 8, 128, 32, [1000, 129], 4),   # MHA: 32-row tile; second sequence leaves splits empty
+    ("bf16", 10, 2, 128, 19, [777], 2),        # 95 rows: partly filled row groups
+    ("bf16", 40, 8, 128, 128, [900, 2100], 5),  # 640 rows: three query blocks
+    ("bf16", 12, 4, 64, 40, [1111], 3),        # head_dim 64
+    ("bf16", 4, 4, 128, 5, [1], 1),            # a single cached row
+]
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,t,plens,n_splits", PREFIX_CASES)
+def test_prefix_splits_alone(dtype, hq, hkv, d, t, plens, n_splits):
+    rng = np.random.default_rng(800 + hq + t)
+    seqs = [synth.make_sequence(rng, dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n_tree=t,
+                                prefix_len=p, parents=synth.tree_chain(t), variant="peaked") for p in plens]
+    w = synth.Workload("case", dtype, len(seqs), hq, hkv, d, t, min(plens), max(plens), None, None, 0)
+    db = DeviceBatch(synth.Batch(w, "peaked", seqs))
+    s = n_splits or ls.ls_prefix_num_splits(db.desc)
+    length = ls.ls_prefix_split_len(db.desc, n_splits)
+    o = torch.full((len(seqs), hq, s, t, d), float("nan"), dtype=torch.float32, device="cuda")
+    l = torch.full((len(seqs), hq, s, t), float("nan"), dtype=torch.float32, device="cuda")
+    say(f"prefix-only {dtype} hq={hq} hkv={hkv} d={d} t={t} plens={plens} splits={s} len={length}")
+    ls.ls_prefix_attn_splitkv(db.desc, db.q, db.k_cache, db.v_cache, db.prefix_lens, n_splits, o, l)
+    torch.cuda.synchronize()
+    o, l = o.cpu().numpy(), l.cpu().numpy()
+    for b, sq in enumerate(seqs):
+        for k in range(s):
+            lo, hi = min(k * length, sq.prefix_len), min((k + 1) * length, sq.prefix_len)
+            if lo == hi:
+                assert np.all(np.isneginf(l[b, :, k])), f"empty split {k} of sequence {b}"
+                continue
+            ro, rl = oracle.attn_all(sq.q, sq.k_cache, sq.v_cache, sq.k_tree, sq.v_tree, sq.parents,
+                                     prefix_lo=lo, prefix_hi=hi, use_tree=False)
+            say(gates(o[b, :, k], l[b, :, k], ro, rl, dtype, f"  b={b} split={k} [{lo},{hi})"))
+
+
+# ----------------------------------------------------------------- the whole path, small ----
+
+@pytest.mark.parametrize("variant", ["iid", "peaked", "tree"])
+def test_full_path_c1(variant):
+    batch = synth.make_batch(synth.WORKLOADS["C1"], variant)
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "f32", f"C1 {variant}"))
+
+
+@pytest.mark.parametrize("name,prefix,variant", [
+    ("C2", 2000, "iid"), ("C2", 2000, "peaked"), ("C2", 2000, "tree"),
+    ("C3", 3100, "peaked"),
+    ("C4", 1777, "iid"), ("C4", 1777, "peaked"), ("C4", 1777, "tree"),
+])
+def test_full_path_reduced_prefix(name, prefix, variant):
+    batch = small(name, prefix, variant)
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", f"{name} P={prefix} {variant}"))
+
+
+@pytest.mark.parametrize("variant", ["iid", "peaked", "tree"])
+def test_full_path_ragged_batch(variant):
+    """The batched shape with per-sequence prefix lengths (and per-sequence trees)."""
+    w = dataclasses.replace(synth.WORKLOADS["C5"], prefix_lo=150, prefix_hi=1900)
+    batch = synth.make_batch(w, variant)
+    assert len(set(batch.prefix_lens.tolist())) == 4
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", f"C5 ragged {variant}"))
+    err = ls.ls_workspace_error(db.desc, db.workspace)
+    assert err >= db.workspace.data_ptr()
+
+
+def test_full_path_token_major_layout():
+    batch = small("C2", 1300, "peaked")
+    db = DeviceBatch(batch, token_major=True)
+    assert db.k_cache.stride(1) == 128 and db.k_cache.stride(2) == 8 * 128
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", "C2 token-major"))
+
+
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_empty_prefix_is_tree_only(name):
+    w = synth.WORKLOADS[name]
+    batch = small(name, 0, "peaked")
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, w.dtype, f"{name} P=0"))
+    # the same through a descriptor that allows a prefix, with device-side length 0
+    batch2 = small(name, 200, "peaked")
+    db2 = DeviceBatch(batch2)
+    db2.prefix_lens.zero_()
+    out2, lse2 = db2.run_full()
+    torch.cuda.synchronize()
+    for s in batch2.seqs:
+        s.k_cache, s.v_cache, s.prefix_len = s.k_cache[:, :0], s.v_cache[:, :0], 0
+    ro2, rl2 = oracle_full(batch2)
+    say(gates(out2.float().cpu().numpy(), lse2.cpu().numpy(), ro2, rl2, w.dtype, f"{name} len=0 on device"))
+
+
+def test_chain_tree_equals_causal_attention_on_device():
+    """Chain-shaped tree: the device result must equal causal attention over [cache || tree]."""
+    w = dataclasses.replace(synth.WORKLOADS["C2"], max_depth=None, max_children=None)
+    batch = synth.make_batch(w, "peaked", prefix_override=700)
+    for s in batch.seqs:
+        s.parents = synth.tree_chain(w.n_tree)
+    db = DeviceBatch(batch)
+    out, _ = db.run_full()
+    torch.cuda.synchronize()
+    s = batch.seqs[0]
+    g = w.group
+    k = torch.from_numpy(np.repeat(np.concatenate([s.k_cache, s.k_tree], axis=1), g, axis=0)).double()[None]
+    v = torch.from_numpy(np.repeat(np.concatenate([s.v_cache, s.v_tree], axis=1), g, axis=0)).double()[None]
+    q = torch.cat([torch.zeros(w.n_q_heads, 700, w.head_dim), torch.from_numpy(s.q)], dim=1).double()[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)[0, :, 700:].numpy()
+    err = np.abs(out[0].float().cpu().numpy() - ref).max()
+    say(f"chain == causal: max_abs={err:.3e}")
+    assert err <= 2e-2 * np.abs(ref).max()
+
+
+def test_repeat_calls_are_bit_identical():
+    batch = small("C2", 2500, "peaked")
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    first_o, first_l = out.clone(), lse.clone()
+    for _ in range(10):
+        out.fill_(float("nan"))
+        db.run_full()
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), first_o.view(torch.int16))
+    assert torch.equal(lse.view(torch.int32), first_l.view(torch.int32))
+
+
+def test_bad_parents_on_device_set_the_error_word():
+    batch = small("C2", 300, "iid")
+    db = DeviceBatch(batch)
+    db.parents[0, 5] = 9
+    db.run_full()
+    torch.cuda.synchronize()
+    addr = ls.ls_workspace_error(db.desc, db.workspace)
+    off = addr - db.workspace.data_ptr()
+    word = db.workspace[off:off + 4].view(torch.int32).cpu().item()
+    assert word == 1
+    assert torch.isfinite(db.out.float()).all()
+
+
+# ------------------------------------------------ the benchmark shapes at full size ----
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_sampled_rows(name):
+    w = synth.WORKLOADS[name]
+    say(f"{name}: drawing inputs")
+    batch = synth.make_batch(w, "iid")
+    db = DeviceBatch(batch)
+    say(f"{name}: prefix lens {batch.prefix_lens.tolist()}, splits {ls.ls_prefix_num_splits(db.desc)}")
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()
+    lse = lse.cpu().numpy()
+    assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
+    rng = np.random.default_rng(w.seed + 99)
+    rows, ro, rl = oracle_full(batch, rows_per_seq=96, rng=rng)
+    got_o = np.stack([out[b, rows[b, :, 0], rows[b, :, 1]] for b in range(w.batch)])
+    got_l = np.stack([lse[b, rows[b, :, 0], rows[b, :, 1]] for b in range(w.batch)])
+    say(gates(got_o, got_l, ro, rl, "bf16", f"{name} full size, 96 sampled rows per sequence"))
+    # a property that holds for every row at any size: with i.i.d. N(0,1) logits the
+    # log-sum-exp sits close to ln(number of visible keys) + 1/2
+    expect = np.log(batch.prefix_lens.astype(np.float64))[:, None, None] + 0.5
+    assert np.abs(lse - expect).max() < 0.5
+
+
+def test_full_size_peaked_c3():
+    w = synth.WORKLOADS["C3"]
+    batch = synth.make_batch(w, "peaked")
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4242)
+    rows, ro, rl = oracle_full(batch, rows_per_seq=96, rng=rng)
+    got_o = out.float().cpu().numpy()[0, rows[0, :, 0], rows[0, :, 1]][None]
+    got_l = lse.cpu().numpy()[0, rows[0, :, 0], rows[0, :, 1]][None]
+    say(gates(got_o, got_l, ro, rl, "bf16", "C3 full size peaked"))

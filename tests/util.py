@@ -1,0 +1,112 @@
+"""Helpers shared by the tests: moving a synthetic batch to the device, running the oracle
+over it, and the error gates."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2502_17421_amd import binding as ls
+from paper_2502_17421_amd import synth
+
+TOL = {"bf16": 2e-2, "f32": 1e-5}          # max-abs bound on out (the stated targets)
+LSE_TOL = {"bf16": 2e-3, "f32": 1e-5}
+
+
+def torch_dtype(name):
+    return torch.bfloat16 if name == "bf16" else torch.float32
+
+
+def to_dev(x, dtype, device="cuda"):
+    """float32 numpy (values exact in dtype) -> device tensor of dtype."""
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device=device, dtype=dtype)
+
+
+class DeviceBatch:
+    """Device tensors of a synth.Batch, [B,H,L,D] layout; ragged prefixes are padded to the
+    longest one with NaN rows that a correct kernel never uses."""
+
+    def __init__(self, batch, device="cuda", token_major=False):
+        w = batch.workload
+        dt = torch_dtype(w.dtype)
+        self.batch = batch
+        self.dtype_name = w.dtype
+        seqs = batch.seqs
+        pmax = max(1, batch.max_prefix_len)
+        hkv, d = seqs[0].k_tree.shape[0], seqs[0].q.shape[2]
+
+        def stack_cache(attr):
+            out = torch.full((len(seqs), hkv, pmax, d), float("nan"), dtype=dt, device=device)
+            for b, s in enumerate(seqs):
+                if s.prefix_len:
+                    out[b, :, :s.prefix_len] = to_dev(getattr(s, attr), dt, device)
+            return out
+
+        def maybe_tm(x):
+            # token-major storage [B,L,H,D] viewed as [B,H,L,D]
+            return x.transpose(1, 2).contiguous().transpose(1, 2) if token_major else x
+
+        self.q = maybe_tm(torch.stack([to_dev(s.q, dt, device) for s in seqs]))
+        self.k_cache = maybe_tm(stack_cache("k_cache"))
+        self.v_cache = maybe_tm(stack_cache("v_cache"))
+        self.k_tree = maybe_tm(torch.stack([to_dev(s.k_tree, dt, device) for s in seqs]))
+        self.v_tree = maybe_tm(torch.stack([to_dev(s.v_tree, dt, device) for s in seqs]))
+        self.parents = torch.from_numpy(np.stack([s.parents for s in seqs])).to(device)
+        self.prefix_lens = torch.from_numpy(batch.prefix_lens).to(device)
+        self.max_prefix_len = batch.max_prefix_len
+        self.out = maybe_tm(torch.full_like(self.q, float("nan")))
+        self.lse = torch.full(self.q.shape[:3], float("nan"), dtype=torch.float32, device=device)
+        self.desc = ls.make_desc(self.q, self.k_cache, self.v_cache, self.k_tree, self.v_tree, self.out,
+                                 self.max_prefix_len)
+        self.workspace = None
+
+    def run_full(self, stream=None):
+        if self.workspace is None:
+            n = ls.ls_workspace_bytes(self.desc)
+            self.workspace = torch.empty(n, dtype=torch.uint8, device=self.q.device)
+        ls.ls_hybrid_tree_attn(self.desc, self.q, self.k_cache, self.v_cache, self.prefix_lens, self.k_tree,
+                               self.v_tree, self.parents, self.out, self.lse, self.workspace, stream=stream)
+        return self.out, self.lse
+
+
+def oracle_full(batch, rows_per_seq=None, rng=None, **kw):
+    """Oracle over a batch.  rows_per_seq=None: every row, returns (out [B,Hq,T,D], lse [B,Hq,T]).
+    Otherwise samples that many (head, row) pairs per sequence and returns
+    (rows [B,n,2], out [B,n,D], lse [B,n])."""
+    outs, lses, rows_all = [], [], []
+    for s in batch.seqs:
+        if rows_per_seq is None:
+            o, l = oracle.attn_all(s.q, s.k_cache, s.v_cache, s.k_tree, s.v_tree, s.parents, **kw)
+        else:
+            hq, t, _ = s.q.shape
+            flat = rng.choice(hq * t, size=min(rows_per_seq, hq * t), replace=False)
+            rows = np.stack([flat // t, flat % t], axis=1).astype(np.int32)
+            o, l = oracle.attn_rows(s.q, s.k_cache, s.v_cache, s.k_tree, s.v_tree, s.parents, rows=rows, **kw)
+            rows_all.append(rows)
+        outs.append(o)
+        lses.append(l)
+    if rows_per_seq is None:
+        return np.stack(outs), np.stack(lses)
+    return np.stack(rows_all), np.stack(outs), np.stack(lses)
+
+
+def gates(got_out, got_lse, ref_out, ref_lse, dtype_name, what=""):
+    """The parity bar: max-abs on out (the stated tolerance), plus the stricter self-imposed
+    gates -- error relative to the largest reference magnitude, normalised RMS, and lse."""
+    got_out = np.asarray(got_out, dtype=np.float64)
+    got_lse = np.asarray(got_lse, dtype=np.float64)
+    assert np.all(np.isfinite(got_out)), f"{what}: non-finite output"
+    err = np.abs(got_out - ref_out)
+    max_abs = float(err.max())
+    scale = float(np.abs(ref_out).max())
+    rms = float(np.sqrt((err ** 2).mean()) / max(np.sqrt((ref_out ** 2).mean()), 1e-30))
+    lse_err = float(np.abs(got_lse - ref_lse).max())
+    info = f"{what}: max_abs={max_abs:.3e} rel_to_max={max_abs / max(scale, 1e-30):.3e} nrms={rms:.3e} lse={lse_err:.3e}"
+    assert max_abs <= TOL[dtype_name], info
+    if dtype_name == "bf16":
+        assert max_abs <= 2e-2 * max(scale, 1e-30), info
+        assert rms <= 5e-3, info
+    else:
+        assert max_abs <= 1e-5 * max(1.0, scale), info
+        assert rms <= 2e-6, info
+    lse_scale = max(1.0, float(np.abs(ref_lse[np.isfinite(ref_lse)]).max())) if dtype_name == "f32" else 1.0
+    assert lse_err <= LSE_TOL[dtype_name] * lse_scale, info
+    return info
