@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid tree attention verify call on one MI355X.
+
+One "step" is one pass of the whole hot path -- tree mask, split-KV attention over the
+cached keys, masked tree attention, LSE merge -- through ls_hybrid_tree_attn, on synthetic
+inputs of the headline shape (8B-class GQA, 32k-token prefix, 64 tree tokens, bf16), already
+resident in HBM.  K/V are rotated over enough independent copies (>= 1 GiB) that no call
+finds its keys in the 256 MB Infinity Cache left there by an earlier call.
+
+Prints ONE JSON line.  `value` is microseconds per verify call (whole job, wall clock over
+the timed steps).  `roofline` is for the dominant kernel (the cached-key attention), timed
+alone with HIP events on the stream it runs on.  `cpu_baseline` is the CPU oracle timed on
+the host cores for the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def algorithmic_bytes_prefix(w, prefix_lens):
+    """Bytes the cached-key kernel must move per launch: K and V rows of every KV head once,
+    plus the queries.  Split partials are overhead and not counted."""
+    e = 2 if w.dtype == "bf16" else 4
+    total = 0
+    for p in prefix_lens:
+        total += 2 * w.n_kv_heads * int(p) * w.head_dim * e + w.n_q_heads * w.n_tree * w.head_dim * e
+    return total
+
+
+def algorithmic_bytes_call(w, prefix_lens):
+    e = 2 if w.dtype == "bf16" else 4
+    total = 0
+    for p in prefix_lens:
+        total += (2 * w.n_kv_heads * int(p) * w.head_dim * e + 2 * w.n_kv_heads * w.n_tree * w.head_dim * e +
+                  2 * w.n_q_heads * w.n_tree * w.head_dim * e + w.n_q_heads * w.n_tree * 4 + w.n_tree * 4)
+    return total
+
+
+def flops_prefix(w, prefix_lens):
+    return sum(4 * w.n_q_heads * w.n_tree * int(p) * w.head_dim for p in prefix_lens)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="C3", help="C1..C5 (the headline metric is quoted on C3)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hot", action="store_true", help="also time with one K/V copy (cache-resident)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2502_17421_amd import binding as ls
+    from paper_2502_17421_amd import synth
+    from util import DeviceBatch
+
+    if not os.path.exists(ls.LIB_PATH):
+        from paper_2502_17421_amd import build as ls_build
+        ls_build.build_library()
+    ls.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    w = synth.WORKLOADS[args.workload]
+    batch = synth.make_batch(w, "iid")
+    db = DeviceBatch(batch)
+    plens = batch.prefix_lens.tolist()
+
+    # cold-cache rotation: independent K/V copies totalling >= 1 GiB
+    kv_bytes = db.k_cache.numel() * db.k_cache.element_size() * 2
+    n_rot = max(2, -(-(1 << 30) // kv_bytes))
+    k_rot = [db.k_cache] + [db.k_cache.clone() for _ in range(n_rot - 1)]
+    v_rot = [db.v_cache] + [db.v_cache.clone() for _ in range(n_rot - 1)]
+    ws = torch.empty(ls.ls_workspace_bytes(db.desc), dtype=torch.uint8, device="cuda")
+    n_splits = ls.ls_prefix_num_splits(db.desc)
+    stream = torch.cuda.current_stream()
+
+    def call(i):
+        r = i % n_rot
+        ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.k_tree, db.v_tree,
+                               db.parents, db.out, db.lse, ws, stream=stream)
+
+    for i in range(args.warmup):
+        call(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        call(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    us_per_call = wall / args.steps * 1e6
+
+    # per-call latency distribution (events around each call)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i, (a, b) in enumerate(evs):
+        a.record(stream)
+        call(i)
+        b.record(stream)
+    torch.cuda.synchronize()
+    lat = np.asarray([a.elapsed_time(b) * 1e3 for a, b in evs])
+
+    # the dominant kernel alone: ls_prefix_attn_splitkv, events around each launch
+    o_part = torch.empty((w.batch, w.n_q_heads, n_splits, w.n_tree, w.head_dim), dtype=torch.float32, device="cuda")
+    l_part = torch.empty((w.batch, w.n_q_heads, n_splits, w.n_tree), dtype=torch.float32, device="cuda")
+
+    def prefix_only(i):
+        r = i % n_rot
+        ls.ls_prefix_attn_splitkv(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, 0, o_part, l_part, stream=stream)
+
+    for i in range(args.warmup):
+        prefix_only(i)
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(evs):
+        a.record(stream)
+        prefix_only(i)
+        b.record(stream)
+    torch.cuda.synchronize()
+    klat = np.asarray([a.elapsed_time(b) * 1e3 for a, b in evs])
+    kernel_us = float(klat.mean())
+
+    hot_us = None
+    if args.hot:
+        for i in range(args.warmup):
+            ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[0], v_rot[0], db.prefix_lens, db.k_tree, db.v_tree,
+                                   db.parents, db.out, db.lse, ws, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[0], v_rot[0], db.prefix_lens, db.k_tree, db.v_tree,
+                                   db.parents, db.out, db.lse, ws, stream=stream)
+        torch.cuda.synchronize()
+        hot_us = (time.perf_counter() - t0) / args.steps * 1e6
+
+    bytes_prefix = algorithmic_bytes_prefix(w, plens)
+    bytes_call = algorithmic_bytes_call(w, plens)
+    fl = flops_prefix(w, plens)
+    t_hbm = bytes_prefix / (HBM_PEAK_GBS * 1e9) * 1e6
+    t_mfma = fl / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6
+    if w.dtype == "bf16" and t_mfma > t_hbm:
+        roof = {"bound": "mfma", "achieved": fl / kernel_us / 1e6, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": bytes_prefix / kernel_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = "prefix_mfma_kernel (ls_prefix_attn_splitkv)"
+    roof["kernel_us"] = kernel_us
+    roof["kernel_us_min"] = float(klat.min())
+    roof["algorithmic_bytes"] = bytes_prefix
+    roof["algorithmic_flops"] = fl
+    roof["hbm_gbs"] = bytes_prefix / kernel_us / 1e3
+    roof["mfma_tflops"] = fl / kernel_us / 1e6
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from util import oracle_full
+        budget = 12.0
+        rows_total = w.batch * w.n_q_heads * w.n_tree
+        rng = np.random.default_rng(7)
+        # a first small sample sizes the run: the whole call if it fits the budget, else a row sample
+        t0 = time.perf_counter()
+        oracle_full(batch, rows_per_seq=16, rng=rng)
+        per_row = (time.perf_counter() - t0) / (16 * w.batch)
+        n_rows = int(min(w.n_q_heads * w.n_tree, max(16, budget / per_row / w.batch)))
+        t0 = time.perf_counter()
+        oracle_full(batch, rows_per_seq=n_rows, rng=rng)
+        dt = time.perf_counter() - t0
+        cpu = {"value": dt / (n_rows * w.batch) * rows_total * 1e6, "unit": "us per verify call", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"{n_rows * w.batch} of {rows_total} query rows of {w.name} (uniform sample per sequence), "
+                         f"{dt:.2f} s measured, scaled to all rows"}
+
+    out = {
+        "metric": "us per verify call (hybrid tree attention, 32k-token prefix)" if w.name == "C3" else
+                  f"us per verify call (hybrid tree attention, workload {w.name})",
+        "value": us_per_call,
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": us_per_call / 1e3,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q heads / {w.n_kv_heads} kv heads, head_dim "
+                               f"{w.head_dim}, prefix {plens}, n_tree {w.n_tree}, seed {w.seed}",
+                   "kv_layout": "[B,Hkv,P,D]", "n_splits": n_splits, "kv_rotation_copies": n_rot,
+                   "kv_rotation_bytes": n_rot * kv_bytes},
+        "call_us": {"mean_wall": us_per_call, "event_min": float(lat.min()), "event_median": float(np.median(lat)),
+                    "event_p90": float(np.percentile(lat, 90))},
+        "call_hbm_gbs": bytes_call / us_per_call / 1e3,
+        "call_tflops": fl / us_per_call / 1e6,
+        "hot_cache_us": hot_us,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
