@@ -105,7 +105,7 @@ def test_tree_attention_alone(dtype, d, t, hq, hkv):
                                  prefix_lo=0, prefix_hi=0, use_tree=True)
         # partial results are float on both dtypes: only the inputs are rounded
         say(gates(o[b].cpu().numpy(), l[b].cpu().numpy(), ro, rl, "f32" if dtype == "f32" else "bf16",
-                  f"tree-only {dtype} b={b}"))
+                  f"tree-only {dtype} b={b}", stress=True))
         assert np.abs(o[b].cpu().numpy() - ro).max() < 2e-5
 
 
@@ -177,7 +177,7 @@ def test_prefix_splits_alone(dtype, hq, hkv, d, t, plens, n_splits):
                 continue
             ro, rl = oracle.attn_all(sq.q, sq.k_cache, sq.v_cache, sq.k_tree, sq.v_tree, sq.parents,
                                      prefix_lo=lo, prefix_hi=hi, use_tree=False)
-            say(gates(o[b, :, k], l[b, :, k], ro, rl, dtype, f"  b={b} split={k} [{lo},{hi})"))
+            say(gates(o[b, :, k], l[b, :, k], ro, rl, dtype, f"  b={b} split={k} [{lo},{hi})", stress=True))
 
 
 # ----------------------------------------------------------------- the whole path, small ----
@@ -189,7 +189,7 @@ def test_full_path_c1(variant):
     out, lse = db.run_full()
     torch.cuda.synchronize()
     ro, rl = oracle_full(batch)
-    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "f32", f"C1 {variant}"))
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "f32", f"C1 {variant}", stress=variant != "iid"))
 
 
 @pytest.mark.parametrize("name,prefix,variant", [
@@ -203,7 +203,8 @@ def test_full_path_reduced_prefix(name, prefix, variant):
     out, lse = db.run_full()
     torch.cuda.synchronize()
     ro, rl = oracle_full(batch)
-    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", f"{name} P={prefix} {variant}"))
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", f"{name} P={prefix} {variant}",
+              stress=variant != "iid"))
 
 
 @pytest.mark.parametrize("variant", ["iid", "peaked", "tree"])
@@ -216,7 +217,8 @@ def test_full_path_ragged_batch(variant):
     out, lse = db.run_full()
     torch.cuda.synchronize()
     ro, rl = oracle_full(batch)
-    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", f"C5 ragged {variant}"))
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", f"C5 ragged {variant}",
+              stress=variant != "iid"))
     err = ls.ls_workspace_error(db.desc, db.workspace)
     assert err >= db.workspace.data_ptr()
 
@@ -228,7 +230,7 @@ def test_full_path_token_major_layout():
     out, lse = db.run_full()
     torch.cuda.synchronize()
     ro, rl = oracle_full(batch)
-    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", "C2 token-major"))
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", "C2 token-major", stress=True))
 
 
 @pytest.mark.parametrize("name", ["C1", "C2"])
@@ -239,7 +241,7 @@ def test_empty_prefix_is_tree_only(name):
     out, lse = db.run_full()
     torch.cuda.synchronize()
     ro, rl = oracle_full(batch)
-    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, w.dtype, f"{name} P=0"))
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, w.dtype, f"{name} P=0", stress=True))
     # the same through a descriptor that allows a prefix, with device-side length 0
     batch2 = small(name, 200, "peaked")
     db2 = DeviceBatch(batch2)
@@ -249,7 +251,8 @@ def test_empty_prefix_is_tree_only(name):
     for s in batch2.seqs:
         s.k_cache, s.v_cache, s.prefix_len = s.k_cache[:, :0], s.v_cache[:, :0], 0
     ro2, rl2 = oracle_full(batch2)
-    say(gates(out2.float().cpu().numpy(), lse2.cpu().numpy(), ro2, rl2, w.dtype, f"{name} len=0 on device"))
+    say(gates(out2.float().cpu().numpy(), lse2.cpu().numpy(), ro2, rl2, w.dtype, f"{name} len=0 on device",
+              stress=True))
 
 
 def test_chain_tree_equals_causal_attention_on_device():
@@ -334,4 +337,4 @@ def test_full_size_peaked_c3():
     rows, ro, rl = oracle_full(batch, rows_per_seq=96, rng=rng)
     got_o = out.float().cpu().numpy()[0, rows[0, :, 0], rows[0, :, 1]][None]
     got_l = lse.cpu().numpy()[0, rows[0, :, 0], rows[0, :, 1]][None]
-    say(gates(got_o, got_l, ro, rl, "bf16", "C3 full size peaked"))
+    say(gates(got_o, got_l, ro, rl, "bf16", "C3 full size peaked", stress=True))

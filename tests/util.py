@@ -88,9 +88,13 @@ def oracle_full(batch, rows_per_seq=None, rng=None, **kw):
     return np.stack(rows_all), np.stack(outs), np.stack(lses)
 
 
-def gates(got_out, got_lse, ref_out, ref_lse, dtype_name, what=""):
+def gates(got_out, got_lse, ref_out, ref_lse, dtype_name, what="", stress=False):
     """The parity bar: max-abs on out (the stated tolerance), plus the stricter self-imposed
-    gates -- error relative to the largest reference magnitude, normalised RMS, and lse."""
+    gates -- error relative to the largest reference magnitude, normalised RMS, and lse.
+
+    stress=True is for the input variants built to give O(1)..O(10) outputs (not the benchmark
+    recipe): there the absolute bound scales with the largest reference magnitude, because
+    rounding the result to bf16 alone costs up to 2^-8 of its magnitude (0.0156 at |x| = 4)."""
     got_out = np.asarray(got_out, dtype=np.float64)
     got_lse = np.asarray(got_lse, dtype=np.float64)
     assert np.all(np.isfinite(got_out)), f"{what}: non-finite output"
@@ -100,7 +104,7 @@ def gates(got_out, got_lse, ref_out, ref_lse, dtype_name, what=""):
     rms = float(np.sqrt((err ** 2).mean()) / max(np.sqrt((ref_out ** 2).mean()), 1e-30))
     lse_err = float(np.abs(got_lse - ref_lse).max())
     info = f"{what}: max_abs={max_abs:.3e} rel_to_max={max_abs / max(scale, 1e-30):.3e} nrms={rms:.3e} lse={lse_err:.3e}"
-    assert max_abs <= TOL[dtype_name], info
+    assert max_abs <= TOL[dtype_name] * (max(1.0, scale) if stress else 1.0), info
     if dtype_name == "bf16":
         assert max_abs <= 2e-2 * max(scale, 1e-30), info
         assert rms <= 5e-3, info
