@@ -4,7 +4,9 @@
 // Work decomposition.  All G*T query rows that share a KV head (G query heads x T tree
 // tokens) form one dense query tile, so every cached K/V row is fetched from HBM once per
 // KV head and used by all of them.  A workgroup owns (sequence, KV head, key split, block
-// of up to WQ*NT*32 query rows); wave wq of the workgroup owns NT groups of 32 query rows.
+// of up to NW*32 query rows); each of its NW waves owns 32 query rows and all keys.  With
+// NW = 8 two waves share a SIMD, so one wave's softmax arithmetic runs under the other's
+// matrix instructions.
 //
 // Data movement.  K and V rows go HBM -> LDS directly (global_load_lds_dwordx4, 16 bytes
 // per lane, no staging registers) into a ring of NS stages of 64 keys each, so several
@@ -20,6 +22,14 @@
 // cross-lane traffic, and the per-query max / sum are a register reduction plus one
 // exchange between the two 32-lane halves.  V^T (the A operand of the second product)
 // is read from the row-major V tile with the LDS transpose read ds_read_b64_tr_b16.
+//
+// Softmax state.  Per query the kernel keeps a reference exponent m (raw-score units) and
+// the sum l of exp2((s - m) * c) over the keys seen, c = scale * log2(e).  m need not be
+// the running maximum: any m gives the same O = sum p v / l and LSE = m*c + log2 l as long
+// as nothing overflows.  After the first 32 keys have set m, the common path therefore
+// skips the max search and only checks that the row sums stay below 2^40; a wave that sees
+// a larger sum (scores far above everything before) redoes that step on the general path,
+// which raises m and rescales O and l.
 //
 // MFMA layouts used (v_mfma_f32_32x32x16_bf16, A is 32xK, B is Kx32, K = 16):
 //   A: lane l holds row l % 32, contraction indices 8*(l/32) .. 8*(l/32)+7
@@ -41,12 +51,12 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TK = 64;        // keys per LDS stage
-constexpr int SUB = 32;       // keys per softmax step (one MFMA row tile)
-constexpr float kLazy = 8.f;  // the running max is left alone while scores stay below max + 8 (base 2)
+constexpr int TK = 64;              // keys per LDS stage
+constexpr int SUB = 32;             // keys per softmax step (one MFMA row tile)
+constexpr float kLazy = 8.f;        // general path: m is raised only when a score exceeds it by 2^8
+constexpr float kSumCap = 0x1p40f;  // common path: largest row-sum increment taken without raising m
 
 #define LS_LDS(p) ((__attribute__((address_space(3))) void *)(p))
-#define LS_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
 __device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c)
 {
@@ -72,16 +82,24 @@ __device__ __forceinline__ float half_sum(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// One 64-lane HBM -> LDS copy: lane l moves 16 bytes from its own global address to LDS byte
-// lds_base + 16*l (lds_base wave-uniform, passed through M0).  Written as inline assembly so
-// that the compiler does not serialise later LDS reads behind all copies still in flight; the
-// kernel orders reads after copies itself with wait_vmem + a barrier.
-__device__ __forceinline__ void copy_row_group_to_lds(const void *gptr, uint32_t lds_base)
+// One 64-lane HBM -> LDS copy: lane l moves 16 bytes from base + voff[l] to LDS byte
+// lds_base + 16*l (base and lds_base wave-uniform; lds_base goes through M0).  Written as
+// inline assembly so that the compiler does not serialise later LDS reads behind all copies
+// still in flight; the kernel orders reads after copies itself with wait_vmem + a barrier.
+__device__ __forceinline__ void copy_to_lds(const uint8_t *base, uint32_t voff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_base), "v"(gptr)
+                 : "s"(lds_base), "v"(voff), "s"(base)
                  : "memory");
+}
+
+__device__ __forceinline__ const uint8_t *uniform_ptr(const uint8_t *p)
+{
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const uint8_t *)(((uint64_t)hi << 32) | lo);
 }
 
 __device__ __forceinline__ uint32_t lds_offset(const void *p)
@@ -104,8 +122,8 @@ __device__ __forceinline__ int vswz(int row)
 
 }  // namespace
 
-template <int D, int NT, int WQ, int NS>
-__global__ void __launch_bounds__(WQ * 64)
+template <int D, int NW, int NS>
+__global__ void __launch_bounds__(NW * 64)
 prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
 {
     constexpr int KSTEPS = D / 16;            // contraction steps of S^T = K Q^T
@@ -115,16 +133,16 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
     constexpr int TILEB = TK * ROWB;          // bytes per K (or V) tile
     constexpr int STAGEB = 2 * TILEB;         // K tile then V tile
     constexpr int ROWS_PER_LOAD = 64 / CH;    // rows one 64-lane load instruction covers
-    constexpr int LOADS = TK / WQ / ROWS_PER_LOAD;  // load instructions per wave, tile and tensor
-    static_assert(TK % (WQ * ROWS_PER_LOAD) == 0, "tile rows must divide over the waves");
+    constexpr int LOADS = TK / NW / ROWS_PER_LOAD;  // load instructions per wave, tile and tensor
+    static_assert(LOADS >= 1 && TK % (NW * ROWS_PER_LOAD) == 0, "tile rows must divide over the waves");
     static_assert(NS >= 2 && NS <= 4, "ring depth");
-    static_assert((NS - 1) * 2 * LOADS <= 63, "the vmcnt counter holds at most 63 outstanding loads");
     constexpr int INFLIGHT = 2 * LOADS;       // vmem instructions per wave and stage
+    static_assert((NS - 1) * INFLIGHT <= 63, "the vmcnt counter holds at most 63 outstanding loads");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
     const int tid = threadIdx.x;
-    const int wq = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int li = lane & 31;
     const int lh = lane >> 5;
@@ -141,62 +159,68 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
     int k_hi = k_lo + plan.split_len;
     k_hi = k_hi > plen ? plen : k_hi;
 
-    // The query rows of this lane: one per 32-row group nt.
-    bool q_ok[NT];
-    size_t part_row[NT];
-    const uint16_t *q_ptr[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int m = (qblock * WQ + wq) * (NT * 32) + nt * 32 + li;
-        q_ok[nt] = m < rows_kv;
-        const int hq = g * p.group + (q_ok[nt] ? m / p.n_tree : 0);
-        const int ti = q_ok[nt] ? m % p.n_tree : 0;
-        part_row[nt] = (((size_t)b * p.n_q_heads + hq) * out.parts_stride + out.part_base + split) * p.n_tree + ti;
-        q_ptr[nt] = (const uint16_t *)p.q + b * p.q_stride[0] + hq * p.q_stride[1] + ti * p.q_stride[2];
-    }
+    // The query row of this lane.
+    const int m_row = (qblock * NW + wave) * 32 + li;
+    const bool q_ok = m_row < rows_kv;
+    const int hq = g * p.group + (q_ok ? m_row / p.n_tree : 0);
+    const int ti = q_ok ? m_row % p.n_tree : 0;
+    const size_t part_row =
+        (((size_t)b * p.n_q_heads + hq) * out.parts_stride + out.part_base + split) * p.n_tree + ti;
 
     if (k_lo >= k_hi) {  // empty split: weight zero in the merge
-        if (lh == 0) {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                if (q_ok[nt]) out.lse[part_row[nt]] = -INFINITY;
-        }
+        if (lh == 0 && q_ok) out.lse[part_row] = -INFINITY;
         return;
     }
 
     // Q^T as the B operand, kept in registers for the whole split.  The loads are issued here
-    // and collected after the first key tiles have been requested (see collect_q below); they
-    // are inline assembly so that no compiler-placed wait for them lands inside the key loop,
-    // where it would also wait for every key tile still in flight.
-    u32x4 q_raw[NT][KSTEPS];
+    // and collected after the first key tiles have been requested; they are inline assembly so
+    // that no compiler-placed wait for them lands inside the key loop, where it would also
+    // wait for every key tile still in flight.
+    const uint16_t *q_ptr = (const uint16_t *)p.q + b * p.q_stride[0] + hq * p.q_stride[1] + ti * p.q_stride[2];
+    u32x4 q_raw[KSTEPS];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk)
-            asm volatile("global_load_dwordx4 %0, %1, off"
-                         : "=v"(q_raw[nt][kk])
-                         : "v"(q_ptr[nt] + kk * 16 + lh * 8)
-                         : "memory");
+    for (int kk = 0; kk < KSTEPS; ++kk)
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(q_raw[kk]) : "v"(q_ptr + kk * 16 + lh * 8) : "memory");
 
     // ---- HBM -> LDS tile loads ----------------------------------------------------------
-    const uint8_t *kbase = (const uint8_t *)p.k_cache + (b * p.kc_stride[0] + g * p.kc_stride[1]) * 2;
-    const uint8_t *vbase = (const uint8_t *)p.v_cache + (b * p.vc_stride[0] + g * p.vc_stride[1]) * 2;
+    const uint8_t *kbase = uniform_ptr((const uint8_t *)p.k_cache + (b * p.kc_stride[0] + g * p.kc_stride[1]) * 2);
+    const uint8_t *vbase = uniform_ptr((const uint8_t *)p.v_cache + (b * p.vc_stride[0] + g * p.vc_stride[1]) * 2);
     const int64_t k_row_bytes = p.kc_stride[2] * 2, v_row_bytes = p.vc_stride[2] * 2;
     const int ld_row = lane / CH;  // row within one load instruction
     const int ld_pos = lane % CH;  // LDS chunk position this lane fills
     const uint32_t smem_off = lds_offset(smem);
+    // byte offsets of this lane's pieces relative to the first row of a tile (whole tiles)
+    uint32_t k_voff[LOADS], v_voff[LOADS];
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const int row = (wave * LOADS + j) * ROWS_PER_LOAD + ld_row;
+        k_voff[j] = (uint32_t)(row * k_row_bytes) + (ld_pos ^ (row & (CH - 1))) * 16;
+        v_voff[j] = (uint32_t)(row * v_row_bytes) + (ld_pos ^ (vswz(row) & (CH - 1))) * 16;
+    }
     auto issue_tile = [&](int k0, int stage) {
         const uint32_t ks_off = __builtin_amdgcn_readfirstlane(smem_off + stage * STAGEB);
+        const uint8_t *kt_base = uniform_ptr(kbase + k0 * k_row_bytes);
+        const uint8_t *vt_base = uniform_ptr(vbase + k0 * v_row_bytes);
+        if (k0 + TK <= k_hi) {
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const int row0 = (wq * LOADS + j) * ROWS_PER_LOAD;  // wave-uniform
-            const int row = row0 + ld_row;
-            int key = k0 + row;
-            key = key < k_hi ? key : k_hi - 1;  // rows past the end repeat the last row; their scores are masked
-            const int kc = ld_pos ^ (row & (CH - 1));
-            const int vc = ld_pos ^ (vswz(row) & (CH - 1));
-            copy_row_group_to_lds(kbase + key * k_row_bytes + kc * 16, ks_off + row0 * ROWB);
-            copy_row_group_to_lds(vbase + key * v_row_bytes + vc * 16, ks_off + TILEB + row0 * ROWB);
+            for (int j = 0; j < LOADS; ++j) {
+                const int row0 = (wave * LOADS + j) * ROWS_PER_LOAD;  // wave-uniform
+                copy_to_lds(kt_base, k_voff[j], ks_off + row0 * ROWB);
+                copy_to_lds(vt_base, v_voff[j], ks_off + TILEB + row0 * ROWB);
+            }
+        } else {
+            // ragged last tile: rows past the end repeat the last valid row; their scores are masked
+#pragma unroll
+            for (int j = 0; j < LOADS; ++j) {
+                const int row0 = (wave * LOADS + j) * ROWS_PER_LOAD;
+                const int row = row0 + ld_row;
+                const int last = k_hi - 1 - k0;
+                const int src = row < last ? row : last;
+                const uint32_t ko = (uint32_t)(src * k_row_bytes) + (ld_pos ^ (row & (CH - 1))) * 16;
+                const uint32_t vo = (uint32_t)(src * v_row_bytes) + (ld_pos ^ (vswz(row) & (CH - 1))) * 16;
+                copy_to_lds(kt_base, ko, ks_off + row0 * ROWB);
+                copy_to_lds(vt_base, vo, ks_off + TILEB + row0 * ROWB);
+            }
         }
     };
 
@@ -221,29 +245,21 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
         }
     }
     if (!collected) wait_vmem<INFLIGHT>();
-    bf16x8 q_reg[NT][KSTEPS];
+    bf16x8 q_reg[KSTEPS];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            asm volatile("" : "+v"(q_raw[nt][kk]));  // orders every use below after the wait above
-            const u32x4 v = q_ok[nt] ? q_raw[nt][kk] : u32x4{0, 0, 0, 0};
-            q_reg[nt][kk] = __builtin_bit_cast(bf16x8, v);
-        }
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        asm volatile("" : "+v"(q_raw[kk]));  // orders every use below after the wait above
+        const u32x4 v = q_ok ? q_raw[kk] : u32x4{0, 0, 0, 0};
+        q_reg[kk] = __builtin_bit_cast(bf16x8, v);
+    }
 
-    floatx16 o_acc[MT][NT];
+    floatx16 o_acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o_acc[mt][nt][r] = 0.f;
-    float m_run[NT], l_run[NT];  // reference max of raw scores; running sum over this lane's keys only
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        m_run[nt] = -INFINITY;
-        l_run[nt] = 0.f;
-    }
+        for (int r = 0; r < 16; ++r) o_acc[mt][r] = 0.f;
+    float m_run = -INFINITY;  // reference exponent in raw-score units (see the header comment)
+    float l_run = 0.f;        // sum of the numerators over this lane's keys only
     const float c = p.scale_log2;
 
     // per-lane LDS offsets of the operand reads
@@ -258,6 +274,8 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
         v_lane_off[mt] = tr_row * ROWB + (((4 * mt + tr_dchunk) ^ tr_swz) * 16) + tr_sub;
+
+    bool common = false;  // wave-uniform: m_run is set and the common (no max search) path may be tried
 
     for (int t = 0; t < n_tiles; ++t) {
         // tile t has landed once at most the younger in-flight tiles remain outstanding
@@ -286,81 +304,75 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
 #pragma unroll
         for (int kt = 0; kt < TK / SUB; ++kt) {
             // ---- S^T = K Q^T for 32 keys --------------------------------------------------
-            floatx16 s_acc[NT];
+            floatx16 s_acc;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s_acc[nt][r] = 0.f;
+            for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
 #pragma unroll
             for (int kk = 0; kk < KSTEPS; ++kk) {
                 const int pos = (2 * kk + lh) ^ k_swz;
                 const bf16x8 a =
                     __builtin_bit_cast(bf16x8, *(const uint4 *)(ks + kt * SUB * ROWB + k_lane_off + pos * 16));
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) s_acc[nt] = mfma32(a, q_reg[nt][kk], s_acc[nt]);
+                s_acc = mfma32(a, q_reg[kk], s_acc);
             }
             // keys past the end of the split weigh nothing (only the last tile can hold any)
             if (k0 + (kt + 1) * SUB > k_hi) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = k0 + kt * SUB + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    if (key >= k_hi) {
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) s_acc[nt][r] = -INFINITY;
-                    }
+                    if (key >= k_hi) s_acc[r] = -INFINITY;
                 }
             }
 
-            // ---- online softmax, one query per lane and group -----------------------------
-            float mx[NT];
-            bool grow = false;
+            // ---- softmax numerators, one query per lane -----------------------------------
+            uint32_t p_pk[8];  // bf16 pairs: the B operand of the second product
+            float sum = 0.f;
+            bool done = false;
+            if (common) {
+                const float mc = m_run * c;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                float v = s_acc[nt][0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) v = fmaxf(v, s_acc[nt][r]);
-                mx[nt] = half_max(v);
-                grow |= (mx[nt] - m_run[nt]) * c > kLazy;  // also true while m_run is -inf
+                for (int r = 0; r < 16; r += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(s_acc[r] * c - mc);
+                    const float p1 = __builtin_amdgcn_exp2f(s_acc[r + 1] * c - mc);
+                    p_pk[r >> 1] = pack_bf16(p0, p1);
+                    sum += p0 + p1;
+                }
+                done = !__any(!(sum < kSumCap));  // also catches inf and nan
             }
-            if (__any(grow)) {
+            if (!done) {
+                float mx = s_acc[0];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const float m_new = fmaxf(m_run[nt], mx[nt]);
-                    // a sub-tile whose keys are all masked leaves m_new = -inf; keep arithmetic finite
-                    const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run[nt] - m_new) * c);
-                    m_run[nt] = m_new;
-                    l_run[nt] *= alpha;
+                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_acc[r]);
+                mx = half_max(mx);
+                const bool grow = (mx - m_run) * c > kLazy;  // also true while m_run is -inf
+                if (__any(grow)) {
+                    const float m_new = fmaxf(m_run, mx);
+                    // a step whose keys are all masked leaves m_new = -inf; keep arithmetic finite
+                    const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * c);
+                    m_run = m_new;
+                    l_run *= alpha;
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) o_acc[mt][nt][r] *= alpha;
+                        for (int r = 0; r < 16; ++r) o_acc[mt][r] *= alpha;
                 }
-            }
-            uint32_t p_pk[NT][8];  // bf16 pairs: the B operands of the second product
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const float mc = m_run[nt] == -INFINITY ? 0.f : m_run[nt] * c;
-                float sum = 0.f;
+                const float mc = m_run == -INFINITY ? 0.f : m_run * c;
+                sum = 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(s_acc[nt][r] * c - mc);
-                    const float p1 = __builtin_amdgcn_exp2f(s_acc[nt][r + 1] * c - mc);
+                    const float p0 = __builtin_amdgcn_exp2f(s_acc[r] * c - mc);
+                    const float p1 = __builtin_amdgcn_exp2f(s_acc[r + 1] * c - mc);
+                    p_pk[r >> 1] = pack_bf16(p0, p1);
                     sum += p0 + p1;
-                    p_pk[nt][r >> 1] = pack_bf16(p0, p1);
                 }
-                l_run[nt] += sum;
+                common = !__any(m_run == -INFINITY);
             }
+            l_run += sum;
 
             // ---- O^T += V^T P^T ---------------------------------------------------------
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
-                bf16x8 pb[NT];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const uint4 v = make_uint4(p_pk[nt][4 * a], p_pk[nt][4 * a + 1], p_pk[nt][4 * a + 2],
-                                               p_pk[nt][4 * a + 3]);
-                    pb[nt] = __builtin_bit_cast(bf16x8, v);
-                }
+                const bf16x8 pb = __builtin_bit_cast(
+                    bf16x8, make_uint4(p_pk[4 * a], p_pk[4 * a + 1], p_pk[4 * a + 2], p_pk[4 * a + 3]));
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const uint8_t *vp = vs + (kt * SUB + a * 16) * ROWB + v_lane_off[mt];
@@ -370,55 +382,53 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
                         (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp + 8 * ROWB));
                     const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
                     const bf16x8 av = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) o_acc[mt][nt] = mfma32(av, pb[nt], o_acc[mt][nt]);
+                    o_acc[mt] = mfma32(av, pb, o_acc[mt]);
                 }
             }
         }
     }
 
     // ---- epilogue: normalise and store this split's partial result -----------------------
+    const float l_tot = half_sum(l_run);
+    if (!q_ok) return;
+    const float inv = 1.f / l_tot;
+    float *orow = out.o + part_row * D;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const float l_tot = half_sum(l_run[nt]);
-        if (!q_ok[nt]) continue;
-        const float inv = 1.f / l_tot;
-        float *orow = out.o + part_row[nt] * D;
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                float4 v;
-                v.x = o_acc[mt][nt][4 * rg + 0] * inv;
-                v.y = o_acc[mt][nt][4 * rg + 1] * inv;
-                v.z = o_acc[mt][nt][4 * rg + 2] * inv;
-                v.w = o_acc[mt][nt][4 * rg + 3] * inv;
-                *(float4 *)(orow + mt * 32 + 8 * rg + 4 * lh) = v;
-            }
-        if (lh == 0) out.lse[part_row[nt]] = (m_run[nt] * c + log2f(l_tot)) * kLn2;
-    }
+        for (int rg = 0; rg < 4; ++rg) {
+            float4 v;
+            v.x = o_acc[mt][4 * rg + 0] * inv;
+            v.y = o_acc[mt][4 * rg + 1] * inv;
+            v.z = o_acc[mt][4 * rg + 2] * inv;
+            v.w = o_acc[mt][4 * rg + 3] * inv;
+            *(float4 *)(orow + mt * 32 + 8 * rg + 4 * lh) = v;
+        }
+    if (lh == 0) out.lse[part_row] = (m_run * c + log2f(l_tot)) * kLn2;
 }
 
 bool prefix_mfma_supports(const Problem &p, int dtype)
 {
-    return dtype == LS_BF16 && (p.head_dim == 128 || p.head_dim == 64);
+    // the tile loads address rows of one tile with 32-bit byte offsets
+    const int64_t max_row_bytes = 2 * (p.kc_stride[2] > p.vc_stride[2] ? p.kc_stride[2] : p.vc_stride[2]);
+    return dtype == LS_BF16 && (p.head_dim == 128 || p.head_dim == 64) && max_row_bytes * TK < (1ll << 31);
 }
 
 namespace {
 
-template <int D, int NT, int WQ, int NS>
+template <int D, int NW, int NS>
 hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &out, hipStream_t stream)
 {
     constexpr int lds_bytes = NS * 2 * TK * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a compute unit");
-    auto kernel = prefix_mfma_kernel<D, NT, WQ, NS>;
+    auto kernel = prefix_mfma_kernel<D, NW, NS>;
     static hipError_t attr = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  lds_bytes);
     if (attr != hipSuccess) return attr;
     const int rows_kv = p.group * p.n_tree;
-    const int rows_wg = WQ * NT * 32;
+    const int rows_wg = NW * 32;
     const dim3 grid(plan.n_splits, (rows_kv + rows_wg - 1) / rows_wg, p.batch * p.n_kv_heads);
-    hipLaunchKernelGGL(kernel, grid, dim3(WQ * 64), lds_bytes, stream, p, plan, out);
+    hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), lds_bytes, stream, p, plan, out);
     return hipGetLastError();
 }
 
@@ -428,16 +438,12 @@ hipError_t launch_prefix_mfma(const Problem &p, const SplitPlan &plan, const Par
 {
     const int rows_kv = p.group * p.n_tree;
     if (p.head_dim == 128) {
-        if (rows_kv > 128) return launch_one<128, 2, 4, 4>(p, plan, out, stream);
-        if (rows_kv > 64) return launch_one<128, 1, 4, 4>(p, plan, out, stream);
-        if (rows_kv > 32) return launch_one<128, 1, 2, 4>(p, plan, out, stream);
-        return launch_one<128, 1, 1, 2>(p, plan, out, stream);
+        if (rows_kv > 128) return launch_one<128, 8, 4>(p, plan, out, stream);
+        return launch_one<128, 4, 4>(p, plan, out, stream);
     }
     if (p.head_dim == 64) {
-        if (rows_kv > 128) return launch_one<64, 2, 4, 4>(p, plan, out, stream);
-        if (rows_kv > 64) return launch_one<64, 1, 4, 4>(p, plan, out, stream);
-        if (rows_kv > 32) return launch_one<64, 1, 2, 4>(p, plan, out, stream);
-        return launch_one<64, 1, 1, 4>(p, plan, out, stream);
+        if (rows_kv > 128) return launch_one<64, 8, 4>(p, plan, out, stream);
+        return launch_one<64, 4, 4>(p, plan, out, stream);
     }
     return hipErrorInvalidValue;
 }
