@@ -116,14 +116,17 @@ int ls_prefix_num_splits(const ls_desc *desc, int32_t *n_splits_out);
 
 /*
  * Bytes of DEVICE workspace ls_hybrid_tree_attn needs for this descriptor:
- * the tree mask, one error word per sequence, and (n_splits + 1) partial outputs and LSEs.
+ * the tree mask, one error word per sequence, and the n_splits partial outputs (stored in
+ * the problem's dtype) and LSEs of the cached part.
  * The workspace must be 256-byte aligned.
  */
 int ls_workspace_bytes(const ls_desc *desc, size_t *bytes_out);
 
 /*
  * The whole path (Section 3.3): tree mask from `parents`, split-KV attention over the
- * cache, masked attention over the tree tokens, log-sum-exp merge into out / lse.
+ * cache, masked attention over the tree tokens, log-sum-exp merge into out / lse.  For
+ * bf16 problems it runs as two launches: the cached-key kernel (whose last workgroups also
+ * build the mask), then one kernel that does the tree attention and the merge per row.
  *
  *   prefix_lens  DEVICE int32[batch]; values are clamped into [0, max_prefix_len].
  *                A sequence with prefix length 0 attends to its tree tokens only.
@@ -166,13 +169,15 @@ int ls_build_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree,
  * rows [s*L, min((s+1)*L, prefix_len)), L = split length derived from max_prefix_len and
  * n_splits (ls_prefix_split_len).  An empty split writes lse = -inf and leaves its output
  * rows untouched.
- *   n_splits  >= 1, or 0 for the library's choice (ls_prefix_num_splits)
- *   o_part    DEVICE float[batch, n_q_heads, n_splits, n_tree, head_dim], normalised
- *   lse_part  DEVICE float[batch, n_q_heads, n_splits, n_tree], natural log
+ *   n_splits    >= 1, or 0 for the library's choice (ls_prefix_num_splits)
+ *   part_dtype  storage type of o_part: LS_F32, or LS_BF16 when desc->dtype is LS_BF16
+ *               (what ls_hybrid_tree_attn uses internally for bf16 problems)
+ *   o_part      DEVICE part_dtype[batch, n_q_heads, n_splits, n_tree, head_dim], normalised
+ *   lse_part    DEVICE float[batch, n_q_heads, n_splits, n_tree], natural log
  */
 int ls_prefix_attn_splitkv(const ls_desc *desc, const void *q,
                            const void *k_cache, const void *v_cache, const int32_t *prefix_lens,
-                           int32_t n_splits, float *o_part, float *lse_part, void *stream);
+                           int32_t n_splits, int32_t part_dtype, void *o_part, float *lse_part, void *stream);
 
 /* Split length L (in cache rows) used for a given n_splits (0 = the library's choice). */
 int ls_prefix_split_len(const ls_desc *desc, int32_t n_splits, int32_t *split_len_out);
@@ -193,12 +198,13 @@ int ls_tree_attn_masked(const ls_desc *desc, const void *q,
  * (d) Log-sum-exp merge of n_parts partial results per query row (Section 3.3
  * "Aggregation", applied associatively).  Parts with lse = -inf are skipped, whatever
  * their output rows hold; if every part is empty the row gets lse = -inf and zeros.
- *   o_parts    DEVICE float[batch, n_q_heads, n_parts, n_tree, head_dim]
+ *   part_dtype storage type of o_parts: LS_F32 or LS_BF16
+ *   o_parts    DEVICE part_dtype[batch, n_q_heads, n_parts, n_tree, head_dim]
  *   lse_parts  DEVICE float[batch, n_q_heads, n_parts, n_tree]
  *   out        DEVICE dtype, strided by desc->o_stride;  lse DEVICE float[batch,n_q_heads,n_tree]
  */
-int ls_lse_merge(const ls_desc *desc, int32_t n_parts,
-                 const float *o_parts, const float *lse_parts,
+int ls_lse_merge(const ls_desc *desc, int32_t n_parts, int32_t part_dtype,
+                 const void *o_parts, const float *lse_parts,
                  void *out, float *lse, void *stream);
 
 #ifdef __cplusplus

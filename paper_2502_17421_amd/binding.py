@@ -66,9 +66,9 @@ def lib() -> ctypes.CDLL:
     L.ls_workspace_error.argtypes = [dp, _vp, ctypes.POINTER(_vp)]
     L.ls_hybrid_tree_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_build_tree_mask.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
-    L.ls_prefix_attn_splitkv.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
+    L.ls_prefix_attn_splitkv.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
     L.ls_tree_attn_masked.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
-    L.ls_lse_merge.argtypes = [dp, _i32, _vp, _vp, _vp, _vp, _vp]
+    L.ls_lse_merge.argtypes = [dp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
     for name in ("ls_validate_desc", "ls_validate_parents_host", "ls_prefix_num_splits", "ls_prefix_split_len",
                  "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_build_tree_mask",
                  "ls_prefix_attn_splitkv", "ls_tree_attn_masked", "ls_lse_merge"):
@@ -201,8 +201,10 @@ def ls_build_tree_mask(parents, mask, err_flag=None, stream=None, check: bool = 
 
 def ls_prefix_attn_splitkv(desc, q, k_cache, v_cache, prefix_lens, n_splits, o_part, lse_part, stream=None,
                            check: bool = True) -> int:
+    """o_part: float32 or bfloat16 tensor [B,Hq,n_splits,T,D]; its dtype selects part_dtype."""
     st = lib().ls_prefix_attn_splitkv(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(prefix_lens),
-                                      int(n_splits), _ptr(o_part), _ptr(lse_part), _stream(stream))
+                                      int(n_splits), _dtype_code(o_part), _ptr(o_part), _ptr(lse_part),
+                                      _stream(stream))
     if check:
         _check(st, "ls_prefix_attn_splitkv")
     return int(st)
@@ -217,8 +219,8 @@ def ls_tree_attn_masked(desc, q, k_tree, v_tree, mask, o_tree, lse_tree, stream=
 
 
 def ls_lse_merge(desc, n_parts, o_parts, lse_parts, out, lse, stream=None, check: bool = True) -> int:
-    st = lib().ls_lse_merge(ctypes.byref(desc), int(n_parts), _ptr(o_parts), _ptr(lse_parts), _ptr(out), _ptr(lse),
-                            _stream(stream))
+    st = lib().ls_lse_merge(ctypes.byref(desc), int(n_parts), _dtype_code(o_parts), _ptr(o_parts), _ptr(lse_parts),
+                            _ptr(out), _ptr(lse), _stream(stream))
     if check:
         _check(st, "ls_lse_merge")
     return int(st)

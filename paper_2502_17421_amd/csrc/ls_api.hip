@@ -105,13 +105,13 @@ Workspace layout(const ls_desc &d, const SplitPlan &plan)
 {
     Workspace w;
     const size_t words = (d.n_tree + 63) / 64;
-    w.n_parts = plan.n_splits + 1;
+    w.n_parts = plan.n_splits;
     const size_t rows = (size_t)d.batch * d.n_q_heads * w.n_parts * d.n_tree;
     w.off_mask = 0;
     w.off_err = align_up(w.off_mask + (size_t)d.batch * d.n_tree * words * sizeof(uint64_t));
     w.off_lse = align_up(w.off_err + (size_t)d.batch * sizeof(int32_t));
     w.off_o = align_up(w.off_lse + rows * sizeof(float));
-    w.total = align_up(w.off_o + rows * d.head_dim * sizeof(float));
+    w.total = align_up(w.off_o + rows * d.head_dim * elem_size(d.dtype));
     return w;
 }
 
@@ -234,23 +234,26 @@ int ls_build_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree, ui
 }
 
 int ls_prefix_attn_splitkv(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
-                           const int32_t *prefix_lens, int32_t n_splits, float *o_part, float *lse_part,
-                           void *stream)
+                           const int32_t *prefix_lens, int32_t n_splits, int32_t part_dtype, void *o_part,
+                           float *lse_part, void *stream)
 {
     const int rc = validate(desc);
     if (rc) return rc;
     if (!q || !prefix_lens || !o_part || !lse_part) return LS_ERR_NULL;
     if (desc->max_prefix_len > 0 && (!k_cache || !v_cache)) return LS_ERR_NULL;
     if (n_splits < 0 || n_splits > 65535) return LS_ERR_SHAPE;
+    if (part_dtype != LS_F32 && part_dtype != LS_BF16) return LS_ERR_DTYPE;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o_part)) return LS_ERR_STRIDE;
     const SplitPlan plan = plan_splits(*desc, n_splits);
     const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, nullptr, nullptr);
-    const Partials out{o_part, lse_part, plan.n_splits, 0};
+    const Partials out{o_part, lse_part, plan.n_splits, 0, part_dtype == LS_BF16};
     hipError_t e;
-    if (prefix_mfma_supports(p, desc->dtype))
-        e = launch_prefix_mfma(p, plan, out, (hipStream_t)stream);
-    else
+    if (prefix_mfma_supports(p, desc->dtype)) {
+        e = launch_prefix_mfma(p, plan, out, MaskJob{nullptr, nullptr, nullptr}, (hipStream_t)stream);
+    } else {
+        if (part_dtype != LS_F32) return LS_ERR_UNSUPPORTED;
         e = launch_prefix_valu(p, desc->dtype, plan, out, (hipStream_t)stream);
+    }
     return e == hipSuccess ? LS_OK : LS_ERR_HIP;
 }
 
@@ -262,20 +265,21 @@ int ls_tree_attn_masked(const ls_desc *desc, const void *q, const void *k_tree, 
     if (!q || !k_tree || !v_tree || !mask || !o_tree || !lse_tree) return LS_ERR_NULL;
     if (!aligned16(q) || !aligned16(k_tree) || !aligned16(v_tree) || !aligned16(o_tree)) return LS_ERR_STRIDE;
     const Problem p = make_problem(*desc, q, nullptr, nullptr, nullptr, k_tree, v_tree);
-    const Partials out{o_tree, lse_tree, 1, 0};
+    const Partials out{o_tree, lse_tree, 1, 0, 0};
     return launch_tree_attn(p, desc->dtype, mask, out, (hipStream_t)stream) == hipSuccess ? LS_OK : LS_ERR_HIP;
 }
 
-int ls_lse_merge(const ls_desc *desc, int32_t n_parts, const float *o_parts, const float *lse_parts, void *out,
-                 float *lse, void *stream)
+int ls_lse_merge(const ls_desc *desc, int32_t n_parts, int32_t part_dtype, const void *o_parts,
+                 const float *lse_parts, void *out, float *lse, void *stream)
 {
     const int rc = validate(desc);
     if (rc) return rc;
     if (!o_parts || !lse_parts || !out || !lse) return LS_ERR_NULL;
     if (n_parts <= 0) return LS_ERR_SHAPE;
+    if (part_dtype != LS_F32 && part_dtype != LS_BF16) return LS_ERR_DTYPE;
     if (!aligned16(o_parts) || !aligned16(out)) return LS_ERR_STRIDE;
-    return launch_merge(desc->batch, desc->n_q_heads, desc->n_tree, desc->head_dim, desc->dtype, n_parts,
-                        o_parts, lse_parts, out, desc->o_stride, lse, (hipStream_t)stream) == hipSuccess
+    return launch_merge(desc->batch, desc->n_q_heads, desc->n_tree, desc->head_dim, desc->dtype, n_parts, o_parts,
+                        part_dtype == LS_BF16, lse_parts, out, desc->o_stride, lse, (hipStream_t)stream) == hipSuccess
                ? LS_OK
                : LS_ERR_HIP;
 }
@@ -300,25 +304,23 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache,
     uint64_t *mask = (uint64_t *)(base + w.off_mask);
     int32_t *err = (int32_t *)(base + w.off_err);
     float *lse_parts = (float *)(base + w.off_lse);
-    float *o_parts = (float *)(base + w.off_o);
+    void *o_parts = base + w.off_o;
     hipStream_t s = (hipStream_t)stream;
     const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree);
 
-    // (b) cached keys -> parts [0, n_splits)
-    const Partials cache_out{o_parts, lse_parts, w.n_parts, 0};
-    hipError_t e;
-    if (prefix_mfma_supports(p, desc->dtype))
-        e = launch_prefix_mfma(p, plan, cache_out, s);
-    else
-        e = launch_prefix_valu(p, desc->dtype, plan, cache_out, s);
-    if (e != hipSuccess) return LS_ERR_HIP;
-    // (a) tree mask, (c) tree keys -> part n_splits
-    if (launch_tree_mask(parents, desc->batch, desc->n_tree, mask, err, s) != hipSuccess) return LS_ERR_HIP;
-    const Partials tree_out{o_parts, lse_parts, w.n_parts, plan.n_splits};
-    if (launch_tree_attn(p, desc->dtype, mask, tree_out, s) != hipSuccess) return LS_ERR_HIP;
-    // (d) merge
-    if (launch_merge(desc->batch, desc->n_q_heads, desc->n_tree, desc->head_dim, desc->dtype, w.n_parts, o_parts,
-                     lse_parts, out, desc->o_stride, lse, s) != hipSuccess)
+    // (b) cached keys -> parts [0, n_splits), stored in the problem's dtype; on the MFMA path
+    // the same launch carries the workgroups of (a), the tree mask
+    const Partials cache_out{o_parts, lse_parts, w.n_parts, 0, desc->dtype == LS_BF16};
+    if (prefix_mfma_supports(p, desc->dtype)) {
+        if (launch_prefix_mfma(p, plan, cache_out, MaskJob{parents, mask, err}, s) != hipSuccess) return LS_ERR_HIP;
+    } else {
+        const Partials f32_out{o_parts, lse_parts, w.n_parts, 0, 0};
+        if (desc->dtype == LS_BF16) return LS_ERR_UNSUPPORTED;  // bf16 row strides beyond the MFMA kernel's range
+        if (launch_prefix_valu(p, desc->dtype, plan, f32_out, s) != hipSuccess) return LS_ERR_HIP;
+        if (launch_tree_mask(parents, desc->batch, desc->n_tree, mask, err, s) != hipSuccess) return LS_ERR_HIP;
+    }
+    // (c) tree keys and (d) merge, one wavefront per query row
+    if (launch_tree_merge(p, desc->dtype, mask, cache_out, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)
         return LS_ERR_HIP;
     return LS_OK;
 }

@@ -26,14 +26,23 @@ struct Problem {
     int64_t q_stride[3], kc_stride[3], vc_stride[3], kt_stride[3], vt_stride[3];
 };
 
-// Where partial results go: o [batch, n_q_heads, parts_stride, n_tree, head_dim] float,
-// lse [batch, n_q_heads, parts_stride, n_tree] float.  A producer writes parts
-// [part_base, part_base + its own count).
+// Where partial results go: o [batch, n_q_heads, parts_stride, n_tree, head_dim] in float or
+// bf16 (o_is_bf16), lse [batch, n_q_heads, parts_stride, n_tree] float.  A producer writes
+// parts [part_base, part_base + its own count).
 struct Partials {
-    float *o;
+    void *o;
     float *lse;
     int32_t parts_stride;
     int32_t part_base;
+    int32_t o_is_bf16;
+};
+
+// Work appended to the cached-key launch so that the whole call needs one launch less:
+// extra workgroups (one per sequence) that build the tree mask.  parents == nullptr: none.
+struct MaskJob {
+    const int32_t *parents;
+    uint64_t *mask;
+    int32_t *err_flag;
 };
 
 struct SplitPlan {
@@ -68,6 +77,41 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// The tree-mask rows of one sequence, computed by the first n_tree threads of a workgroup
+// (all threads of the workgroup must call it; it synchronises them once).
+__device__ __forceinline__ void build_tree_mask_rows(const int32_t *__restrict__ par, int32_t n_tree,
+                                                     uint64_t *__restrict__ mask_rows,
+                                                     int32_t *__restrict__ err_word, int tid)
+{
+    constexpr int WORDS = LS_MAX_TREE / 64;
+    uint64_t bits[WORDS];
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) bits[w] = 0;
+    int bad = 0;
+    int j = tid < n_tree ? tid : -1;
+    // the chain index strictly decreases, so the walk ends after at most tid steps whatever
+    // the array holds; an entry outside {-1} u [0, j) ends the walk and is reported
+    while (j >= 0) {
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w)
+            if ((j >> 6) == w) bits[w] |= (uint64_t)1 << (j & 63);
+        int p = par[j];
+        if (p < -1 || p >= j) {
+            bad = 1;
+            p = -1;
+        }
+        j = p;
+    }
+    if (tid < n_tree) {
+        const int words = (n_tree + 63) >> 6;
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w)
+            if (w < words) mask_rows[(size_t)tid * words + w] = bits[w];
+    }
+    const int any_bad = __syncthreads_or(bad);
+    if (tid == 0 && err_word) *err_word = any_bad ? 1 : 0;
+}
+
 // Host launchers, one per kernel family.  Each returns a hipError_t from the launch.
 hipError_t launch_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree, uint64_t *mask,
                             int32_t *err_flag, hipStream_t stream);
@@ -75,12 +119,16 @@ hipError_t launch_tree_attn(const Problem &p, int dtype, const uint64_t *mask, c
                             hipStream_t stream);
 hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
                               hipStream_t stream);
-hipError_t launch_prefix_mfma(const Problem &p, const SplitPlan &plan, const Partials &out,
+hipError_t launch_prefix_mfma(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
                               hipStream_t stream);
 bool prefix_mfma_supports(const Problem &p, int dtype);
 SplitPlan plan_splits(const ls_desc &d, int32_t n_splits_request);
 hipError_t launch_merge(int32_t batch, int32_t n_q_heads, int32_t n_tree, int32_t head_dim, int dtype,
-                        int32_t n_parts, const float *o_parts, const float *lse_parts, void *out,
+                        int32_t n_parts, const void *o_parts, int parts_are_bf16, const float *lse_parts, void *out,
                         const int64_t o_stride[3], float *lse, hipStream_t stream);
+// Masked tree attention and the merge with n_cache_parts cached-key partials in one kernel.
+hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, const Partials &cache_parts,
+                             int32_t n_cache_parts, void *out, const int64_t o_stride[3], float *lse,
+                             hipStream_t stream);
 
 }  // namespace ls

@@ -124,7 +124,7 @@ __device__ __forceinline__ int vswz(int row)
 
 template <int D, int NW, int NS>
 __global__ void __launch_bounds__(NW * 64)
-prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
+prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, int32_t n_qblocks)
 {
     constexpr int KSTEPS = D / 16;            // contraction steps of S^T = K Q^T
     constexpr int MT = D / 32;                // 32-row tiles of O^T along head_dim
@@ -140,17 +140,30 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
     static_assert((NS - 1) * INFLIGHT <= 63, "the vmcnt counter holds at most 63 outstanding loads");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-
     const int tid = threadIdx.x;
+
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int li = lane & 31;
     const int lh = lane >> 5;
 
-    const int split = blockIdx.x;
-    const int qblock = blockIdx.y;
-    const int b = blockIdx.z / p.n_kv_heads;
-    const int g = blockIdx.z % p.n_kv_heads;
+    // Linear workgroup index: key split fastest, then query block, then (sequence, KV head).
+    // Workgroups past that range (one per sequence, present only in the whole-path launch)
+    // build the tree mask, which the kernel that follows this one consumes.
+    const int n_main = plan.n_splits * n_qblocks * p.batch * p.n_kv_heads;
+    if ((int)blockIdx.x >= n_main) {
+        const int mb = blockIdx.x - n_main;
+        const int words = (p.n_tree + 63) >> 6;
+        build_tree_mask_rows(mask_job.parents + (size_t)mb * p.n_tree, p.n_tree,
+                             mask_job.mask + (size_t)mb * p.n_tree * words,
+                             mask_job.err_flag ? mask_job.err_flag + mb : nullptr, tid);
+        return;
+    }
+    const int split = blockIdx.x % plan.n_splits;
+    const int qblock = (blockIdx.x / plan.n_splits) % n_qblocks;
+    const int bz = blockIdx.x / (plan.n_splits * n_qblocks);
+    const int b = bz / p.n_kv_heads;
+    const int g = bz % p.n_kv_heads;
     const int rows_kv = p.group * p.n_tree;
 
     int plen = p.prefix_lens[b];
@@ -301,6 +314,21 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
         const uint8_t *vs = ks + TILEB;
         const int k0 = k_lo + t * TK;
 
+        // Operand fragments are fetched from LDS a step ahead of the matrix instructions that
+        // use them: K for step 0 right after the barrier, then inside step kt the V fragments of
+        // kt and the K fragments of kt+1 are requested before the softmax arithmetic so that
+        // they land under it.
+        bf16x8 k_frag[KSTEPS];
+        auto fetch_k = [&](int kt) {
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+                const int pos = (2 * kk + lh) ^ k_swz;
+                k_frag[kk] =
+                    __builtin_bit_cast(bf16x8, *(const uint4 *)(ks + kt * SUB * ROWB + k_lane_off + pos * 16));
+            }
+        };
+        fetch_k(0);
+
 #pragma unroll
         for (int kt = 0; kt < TK / SUB; ++kt) {
             // ---- S^T = K Q^T for 32 keys --------------------------------------------------
@@ -308,12 +336,25 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) {
-                const int pos = (2 * kk + lh) ^ k_swz;
-                const bf16x8 a =
-                    __builtin_bit_cast(bf16x8, *(const uint4 *)(ks + kt * SUB * ROWB + k_lane_off + pos * 16));
-                s_acc = mfma32(a, q_reg[kk], s_acc);
-            }
+            for (int kk = 0; kk < KSTEPS; ++kk) s_acc = mfma32(k_frag[kk], q_reg[kk], s_acc);
+            __builtin_amdgcn_sched_barrier(0);
+
+            bf16x8 v_frag[2][MT];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const uint8_t *vp = vs + (kt * SUB + a * 16) * ROWB + v_lane_off[mt];
+                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp));
+                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp + 8 * ROWB));
+                    const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+                    v_frag[a][mt] = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
+                }
+            if (kt + 1 < TK / SUB) fetch_k(kt + 1);
+            __builtin_amdgcn_sched_barrier(0);
+
             // keys past the end of the split weigh nothing (only the last tile can hold any)
             if (k0 + (kt + 1) * SUB > k_hi) {
 #pragma unroll
@@ -374,16 +415,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
                 const bf16x8 pb = __builtin_bit_cast(
                     bf16x8, make_uint4(p_pk[4 * a], p_pk[4 * a + 1], p_pk[4 * a + 2], p_pk[4 * a + 3]));
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const uint8_t *vp = vs + (kt * SUB + a * 16) * ROWB + v_lane_off[mt];
-                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp));
-                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp + 8 * ROWB));
-                    const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
-                    const bf16x8 av = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
-                    o_acc[mt] = mfma32(av, pb, o_acc[mt]);
-                }
+                for (int mt = 0; mt < MT; ++mt) o_acc[mt] = mfma32(v_frag[a][mt], pb, o_acc[mt]);
             }
         }
     }
@@ -392,18 +424,31 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out)
     const float l_tot = half_sum(l_run);
     if (!q_ok) return;
     const float inv = 1.f / l_tot;
-    float *orow = out.o + part_row * D;
+    if (out.o_is_bf16) {
+        uint16_t *orow = (uint16_t *)out.o + part_row * D;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-            float4 v;
-            v.x = o_acc[mt][4 * rg + 0] * inv;
-            v.y = o_acc[mt][4 * rg + 1] * inv;
-            v.z = o_acc[mt][4 * rg + 2] * inv;
-            v.w = o_acc[mt][4 * rg + 3] * inv;
-            *(float4 *)(orow + mt * 32 + 8 * rg + 4 * lh) = v;
-        }
+            for (int rg = 0; rg < 4; ++rg) {
+                uint2 v;
+                v.x = pack_bf16(o_acc[mt][4 * rg + 0] * inv, o_acc[mt][4 * rg + 1] * inv);
+                v.y = pack_bf16(o_acc[mt][4 * rg + 2] * inv, o_acc[mt][4 * rg + 3] * inv);
+                *(uint2 *)(orow + mt * 32 + 8 * rg + 4 * lh) = v;
+            }
+    } else {
+        float *orow = (float *)out.o + part_row * D;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                float4 v;
+                v.x = o_acc[mt][4 * rg + 0] * inv;
+                v.y = o_acc[mt][4 * rg + 1] * inv;
+                v.z = o_acc[mt][4 * rg + 2] * inv;
+                v.w = o_acc[mt][4 * rg + 3] * inv;
+                *(float4 *)(orow + mt * 32 + 8 * rg + 4 * lh) = v;
+            }
+    }
     if (lh == 0) out.lse[part_row] = (m_run * c + log2f(l_tot)) * kLn2;
 }
 
@@ -417,33 +462,40 @@ bool prefix_mfma_supports(const Problem &p, int dtype)
 namespace {
 
 template <int D, int NW, int NS>
-hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &out, hipStream_t stream)
+hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
+                      hipStream_t stream)
 {
     constexpr int lds_bytes = NS * 2 * TK * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a compute unit");
+    static_assert(NW * 64 >= LS_MAX_TREE, "the mask workgroups need one thread per tree token");
     auto kernel = prefix_mfma_kernel<D, NW, NS>;
     static hipError_t attr = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  lds_bytes);
     if (attr != hipSuccess) return attr;
     const int rows_kv = p.group * p.n_tree;
     const int rows_wg = NW * 32;
-    const dim3 grid(plan.n_splits, (rows_kv + rows_wg - 1) / rows_wg, p.batch * p.n_kv_heads);
-    hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), lds_bytes, stream, p, plan, out);
+    const int n_qblocks = (rows_kv + rows_wg - 1) / rows_wg;
+    const int64_t n_main = (int64_t)plan.n_splits * n_qblocks * p.batch * p.n_kv_heads;
+    const int64_t n_blocks = n_main + (mask_job.parents ? p.batch : 0);
+    if (n_blocks > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), lds_bytes, stream, p, plan, out, mask_job,
+                       n_qblocks);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_prefix_mfma(const Problem &p, const SplitPlan &plan, const Partials &out, hipStream_t stream)
+hipError_t launch_prefix_mfma(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
+                              hipStream_t stream)
 {
     const int rows_kv = p.group * p.n_tree;
     if (p.head_dim == 128) {
-        if (rows_kv > 128) return launch_one<128, 8, 4>(p, plan, out, stream);
-        return launch_one<128, 4, 4>(p, plan, out, stream);
+        if (rows_kv > 128) return launch_one<128, 8, 4>(p, plan, out, mask_job, stream);
+        return launch_one<128, 4, 4>(p, plan, out, mask_job, stream);
     }
     if (p.head_dim == 64) {
-        if (rows_kv > 128) return launch_one<64, 8, 4>(p, plan, out, stream);
-        return launch_one<64, 4, 4>(p, plan, out, stream);
+        if (rows_kv > 128) return launch_one<64, 8, 4>(p, plan, out, mask_job, stream);
+        return launch_one<64, 4, 4>(p, plan, out, mask_job, stream);
     }
     return hipErrorInvalidValue;
 }

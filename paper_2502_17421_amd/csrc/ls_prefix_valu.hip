@@ -126,7 +126,7 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
         (((size_t)b * p.n_q_heads + hq) * out.parts_stride + out.part_base + split) * p.n_tree + ti;
     if (l_run > 0.f) {
         const float inv = 1.f / l_run;
-        float *orow = out.o + prow * D;
+        float *orow = (float *)out.o + prow * D;
 #pragma unroll
         for (int k = 0; k < D / 8; ++k) orow[c + 8 * k] = acc[k] * inv;
         if (c == 0) out.lse[prow] = (m_run + log2f(l_run)) * kLn2;

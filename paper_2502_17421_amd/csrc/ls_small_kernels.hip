@@ -1,55 +1,26 @@
-// The three small kernels of the path: tree-mask builder, masked tree attention,
-// log-sum-exp merge.  (LongSpec, Section 3.3; the aggregation appendix.)
+// The small kernels of the path: tree-mask builder, masked tree attention, log-sum-exp
+// merge, and the fused tree attention + merge that closes the whole call.  (LongSpec, Section 3.3; the aggregation appendix.)
 #include "ls_internal.hpp"
 
 namespace ls {
 
 // --------------------------------------------------------------------------- (a) ----
-// Tree mask: thread i walks the parent chain of node i and sets one bit per node met,
-// itself included.  The chain index strictly decreases, so the walk ends after at most
-// i steps whatever the array holds; an entry outside {-1} u [0, j) ends the walk and is
-// reported in err_flag[b] (written 0 or 1 on every launch).
-template <int WORDS>
+// Tree mask: one workgroup per sequence; thread i walks the parent chain of node i and sets
+// one bit per node met, itself included.  err_flag[b] is written 0 or 1 on every launch.
 __global__ void __launch_bounds__(LS_MAX_TREE)
 tree_mask_kernel(const int32_t *__restrict__ parents, int32_t n_tree, uint64_t *__restrict__ mask,
                  int32_t *__restrict__ err_flag)
 {
     const int b = blockIdx.x;
-    const int i = threadIdx.x;
-    const int32_t *par = parents + (size_t)b * n_tree;
-    uint64_t bits[WORDS];
-#pragma unroll
-    for (int w = 0; w < WORDS; ++w) bits[w] = 0;
-    int bad = 0;
-    int j = i < n_tree ? i : -1;
-    while (j >= 0) {
-#pragma unroll
-        for (int w = 0; w < WORDS; ++w)
-            if ((j >> 6) == w) bits[w] |= (uint64_t)1 << (j & 63);
-        int p = par[j];
-        if (p < -1 || p >= j) {
-            bad = 1;
-            p = -1;
-        }
-        j = p;
-    }
-    if (i < n_tree) {
-        const int words = (n_tree + 63) >> 6;
-        uint64_t *row = mask + ((size_t)b * n_tree + i) * words;
-#pragma unroll
-        for (int w = 0; w < WORDS; ++w)
-            if (w < words) row[w] = bits[w];
-    }
-    const int any_bad = __syncthreads_or(bad);
-    if (i == 0 && err_flag) err_flag[b] = any_bad ? 1 : 0;
+    const int words = (n_tree + 63) >> 6;
+    build_tree_mask_rows(parents + (size_t)b * n_tree, n_tree, mask + (size_t)b * n_tree * words,
+                         err_flag ? err_flag + b : nullptr, threadIdx.x);
 }
 
 hipError_t launch_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree, uint64_t *mask,
                             int32_t *err_flag, hipStream_t stream)
 {
-    static_assert(LS_MAX_TREE == 128, "two mask words");
-    hipLaunchKernelGGL(tree_mask_kernel<2>, dim3(batch), dim3(LS_MAX_TREE), 0, stream, parents, n_tree,
-                       mask, err_flag);
+    hipLaunchKernelGGL(tree_mask_kernel, dim3(batch), dim3(LS_MAX_TREE), 0, stream, parents, n_tree, mask, err_flag);
     return hipGetLastError();
 }
 
@@ -108,7 +79,7 @@ tree_attn_kernel(Problem p, const uint64_t *__restrict__ mask, Partials out)
         }
     }
     const size_t prow = (((size_t)b * p.n_q_heads + h) * out.parts_stride + out.part_base) * p.n_tree + i;
-    float *orow = out.o + prow * D;
+    float *orow = (float *)out.o + prow * D;
     const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) orow[lane * EPL + e] = acc[e] * inv;
@@ -136,10 +107,18 @@ hipError_t launch_tree_attn(const Problem &p, int dtype, const uint64_t *mask, c
 // the largest part LSE, second pass accumulates exp(LSE_k - max) weighted outputs and the
 // weight sum; the result is out = sum_k w_k O_k / sum_k w_k, lse = max + log(sum_k w_k),
 // which is the two-term aggregation rule of Section 3.3 applied to all parts at once.
-template <typename T, int D>
+__device__ __forceinline__ float4 load4(const float *p) { return *(const float4 *)p; }
+__device__ __forceinline__ float4 load4(const uint16_t *p)
+{
+    const uint2 v = *(const uint2 *)p;
+    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                       __uint_as_float(v.y & 0xffff0000u));
+}
+
+template <typename T, typename PT, int D>
 __global__ void __launch_bounds__(256)
 merge_kernel(int32_t rows_total, int32_t n_q_heads, int32_t n_tree, int32_t n_parts,
-             const float *__restrict__ o_parts, const float *__restrict__ lse_parts, T *__restrict__ out,
+             const PT *__restrict__ o_parts, const float *__restrict__ lse_parts, T *__restrict__ out,
              int64_t os0, int64_t os1, int64_t os2, float *__restrict__ lse)
 {
     constexpr int TPR = D / 4;  // threads per row
@@ -162,7 +141,7 @@ merge_kernel(int32_t rows_total, int32_t n_q_heads, int32_t n_tree, int32_t n_pa
             const float l = lp[(size_t)k * n_tree];
             if (l == -INFINITY) continue;
             const float w = exp2f((l - top) * kLog2e);
-            const float4 o = *(const float4 *)(o_parts + ((bh * n_parts + k) * n_tree + i) * D + c);
+            const float4 o = load4(o_parts + ((bh * n_parts + k) * n_tree + i) * D + c);
             acc.x += w * o.x;
             acc.y += w * o.y;
             acc.z += w * o.z;
@@ -180,21 +159,202 @@ merge_kernel(int32_t rows_total, int32_t n_q_heads, int32_t n_tree, int32_t n_pa
 }
 
 hipError_t launch_merge(int32_t batch, int32_t n_q_heads, int32_t n_tree, int32_t head_dim, int dtype,
-                        int32_t n_parts, const float *o_parts, const float *lse_parts, void *out,
+                        int32_t n_parts, const void *o_parts, int parts_are_bf16, const float *lse_parts, void *out,
                         const int64_t o_stride[3], float *lse, hipStream_t stream)
 {
     const int rows = batch * n_q_heads * n_tree;
     const int threads = rows * (head_dim / 4);
     const dim3 block(256), grid((threads + 255) / 256);
-#define LS_MERGE_CASE(T, DD)                                                                           \
-    hipLaunchKernelGGL((merge_kernel<T, DD>), grid, block, 0, stream, rows, n_q_heads, n_tree, n_parts, \
-                       o_parts, lse_parts, (T *)out, o_stride[0], o_stride[1], o_stride[2], lse)
-    if (dtype == LS_BF16 && head_dim == 128) LS_MERGE_CASE(uint16_t, 128);
-    else if (dtype == LS_BF16 && head_dim == 64) LS_MERGE_CASE(uint16_t, 64);
-    else if (dtype == LS_F32 && head_dim == 128) LS_MERGE_CASE(float, 128);
-    else if (dtype == LS_F32 && head_dim == 64) LS_MERGE_CASE(float, 64);
-    else return hipErrorInvalidValue;
+#define LS_MERGE_CASE(T, PT, DD)                                                                              \
+    hipLaunchKernelGGL((merge_kernel<T, PT, DD>), grid, block, 0, stream, rows, n_q_heads, n_tree, n_parts,     \
+                       (const PT *)o_parts, lse_parts, (T *)out, o_stride[0], o_stride[1], o_stride[2], lse)
+    const int key = (dtype == LS_BF16 ? 0 : 1) | (parts_are_bf16 ? 2 : 0) | (head_dim == 128 ? 4 : 0);
+    if (head_dim != 64 && head_dim != 128) return hipErrorInvalidValue;
+    switch (key) {
+    case 0: LS_MERGE_CASE(uint16_t, float, 64); break;
+    case 1: LS_MERGE_CASE(float, float, 64); break;
+    case 2: LS_MERGE_CASE(uint16_t, uint16_t, 64); break;
+    case 3: LS_MERGE_CASE(float, uint16_t, 64); break;
+    case 4: LS_MERGE_CASE(uint16_t, float, 128); break;
+    case 5: LS_MERGE_CASE(float, float, 128); break;
+    case 6: LS_MERGE_CASE(uint16_t, uint16_t, 128); break;
+    default: LS_MERGE_CASE(float, uint16_t, 128); break;
+    }
 #undef LS_MERGE_CASE
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------- (c) + (d) fused ----
+// The tail of the whole path: one wavefront per query row computes the masked tree attention
+// of that row (as tree_attn_kernel does, keeping the result in registers) and merges it with
+// the row's cached-key partials by the aggregation rule of Section 3.3.  The head dimension
+// is spread over the 64 lanes; logits and part weights are wavefront reductions.
+template <int EPL> struct Piece;
+template <> struct Piece<1> {
+    static __device__ __forceinline__ void load(const float *p, float *v) { v[0] = p[0]; }
+    static __device__ __forceinline__ void load(const uint16_t *p, float *v) { v[0] = bf16_to_float(p[0]); }
+    static __device__ __forceinline__ void store(float *p, const float *v) { p[0] = v[0]; }
+    static __device__ __forceinline__ void store(uint16_t *p, const float *v) { p[0] = float_to_bf16(v[0]); }
+};
+template <> struct Piece<2> {
+    static __device__ __forceinline__ void load(const float *p, float *v)
+    {
+        const float2 t = *(const float2 *)p;
+        v[0] = t.x;
+        v[1] = t.y;
+    }
+    static __device__ __forceinline__ void load(const uint16_t *p, float *v)
+    {
+        const uint32_t t = *(const uint32_t *)p;
+        v[0] = __uint_as_float(t << 16);
+        v[1] = __uint_as_float(t & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(float *p, const float *v) { *(float2 *)p = make_float2(v[0], v[1]); }
+    static __device__ __forceinline__ void store(uint16_t *p, const float *v)
+    {
+        *(uint32_t *)p = (uint32_t)float_to_bf16(v[0]) | ((uint32_t)float_to_bf16(v[1]) << 16);
+    }
+};
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+template <typename T, typename PT, int D>
+__global__ void __launch_bounds__(256)
+tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, int32_t n_cache, T *__restrict__ out,
+                  int64_t os0, int64_t os1, int64_t os2, float *__restrict__ lse)
+{
+    constexpr int EPL = D / kWave;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int row = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int rows_total = p.batch * p.n_q_heads * p.n_tree;
+    if (row >= rows_total) return;
+    const int i = row % p.n_tree;
+    const int h = (row / p.n_tree) % p.n_q_heads;
+    const int b = row / (p.n_tree * p.n_q_heads);
+    const int g = h / p.group;
+    const int words = (p.n_tree + 63) >> 6;
+
+    // part weights first, so that their loads are in flight during the tree part
+    const size_t prow0 = (((size_t)b * p.n_q_heads + h) * parts.parts_stride + parts.part_base) * p.n_tree + i;
+    const float *lp = parts.lse + prow0;
+    const PT *op = (const PT *)parts.o + prow0 * D + lane * EPL;
+    const size_t part_step = (size_t)p.n_tree * D;  // elements between consecutive parts of one row
+
+    // ---- masked attention over the tree keys (unnormalised, base-2 logits) ----------------
+    const T *qrow = (const T *)p.q + b * p.q_stride[0] + h * p.q_stride[1] + i * p.q_stride[2];
+    const T *kbase = (const T *)p.k_tree + b * p.kt_stride[0] + g * p.kt_stride[1];
+    const T *vbase = (const T *)p.v_tree + b * p.vt_stride[0] + g * p.vt_stride[1];
+    const uint64_t *mrow = mask + ((size_t)b * p.n_tree + i) * words;
+    float qv[EPL], acc[EPL];
+    Piece<EPL>::load(qrow + lane * EPL, qv);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        qv[e] *= p.scale_log2;
+        acc[e] = 0.f;
+    }
+    float m_run = -INFINITY, l_run = 0.f;
+    for (int w = 0; w < words; ++w) {
+        uint64_t bits = mrow[w];
+        if (w == words - 1 && (p.n_tree & 63)) bits &= ((uint64_t)1 << (p.n_tree & 63)) - 1;
+        while (bits) {
+            const int j = (w << 6) + __builtin_ctzll(bits);
+            bits &= bits - 1;
+            float kv[EPL], vv[EPL];
+            Piece<EPL>::load(kbase + j * p.kt_stride[2] + lane * EPL, kv);
+            Piece<EPL>::load(vbase + j * p.vt_stride[2] + lane * EPL, vv);
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) part += qv[e] * kv[e];
+            const float z = wave_sum(part);
+            const float m_new = fmaxf(m_run, z);
+            const float alpha = exp2f(m_run - m_new);
+            const float pj = exp2f(z - m_new);
+            l_run = l_run * alpha + pj;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * alpha + pj * vv[e];
+            m_run = m_new;
+        }
+    }
+    const float lse_tree = l_run > 0.f ? (m_run + log2f(l_run)) * kLn2 : -INFINITY;
+
+    // ---- merge --------------------------------------------------------------------------
+    float top = lse_tree;
+    for (int s0 = 0; s0 < n_cache; s0 += kWave) {
+        const int s = s0 + lane;
+        const float l = s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY;
+        top = fmaxf(top, wave_max(l));
+    }
+    T *orow = out + b * os0 + h * os1 + i * os2 + lane * EPL;
+    float o[EPL];
+    if (top == -INFINITY) {  // no visible key at all
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[e] = 0.f;
+        Piece<EPL>::store(orow, o);
+        if (lane == 0) lse[row] = -INFINITY;
+        return;
+    }
+    const float w_tree = l_run > 0.f ? exp2f((lse_tree - top) * kLog2e) : 0.f;
+    const float tree_scale = l_run > 0.f ? w_tree / l_run : 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[e] = acc[e] * tree_scale;
+    float w_lane = 0.f;  // this lane's part weights, summed over the 64-part chunks
+    for (int s0 = 0; s0 < n_cache; s0 += kWave) {
+        const int s = s0 + lane;
+        const float l = s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY;
+        const float w = l == -INFINITY ? 0.f : exp2f((l - top) * kLog2e);
+        w_lane += w;
+        const int cnt = n_cache - s0 < kWave ? n_cache - s0 : kWave;
+        for (int k8 = 0; k8 < cnt; k8 += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                // past the last part the lane weight is 0 and the (clamped) address is still valid
+                const int k = k8 + u;
+                const int part = s0 + k < n_cache ? s0 + k : n_cache - 1;
+                const float wk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), k));
+                float v[EPL];
+                Piece<EPL>::load(op + (size_t)part * part_step, v);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) o[e] += wk > 0.f ? wk * v[e] : 0.f;  // empty parts may hold anything
+            }
+        }
+    }
+    const float wsum = wave_sum(w_lane) + w_tree;
+    const float inv = 1.f / wsum;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[e] *= inv;
+    Piece<EPL>::store(orow, o);
+    if (lane == 0) lse[row] = top + log2f(wsum) * kLn2;
+}
+
+hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, const Partials &cache_parts,
+                             int32_t n_cache_parts, void *out, const int64_t o_stride[3], float *lse,
+                             hipStream_t stream)
+{
+    const int rows = p.batch * p.n_q_heads * p.n_tree;
+    const dim3 block(256), grid((rows + 3) / 4);
+#define LS_TM_CASE(T, PT, DD)                                                                                  \
+    hipLaunchKernelGGL((tree_merge_kernel<T, PT, DD>), grid, block, 0, stream, p, mask, cache_parts, n_cache_parts, \
+                       (T *)out, o_stride[0], o_stride[1], o_stride[2], lse)
+    if (p.head_dim != 64 && p.head_dim != 128) return hipErrorInvalidValue;
+    if (dtype == LS_BF16) {
+        if (cache_parts.o_is_bf16) {
+            if (p.head_dim == 128) LS_TM_CASE(uint16_t, uint16_t, 128);
+            else LS_TM_CASE(uint16_t, uint16_t, 64);
+        } else {
+            if (p.head_dim == 128) LS_TM_CASE(uint16_t, float, 128);
+            else LS_TM_CASE(uint16_t, float, 64);
+        }
+    } else {
+        if (cache_parts.o_is_bf16) return hipErrorInvalidValue;
+        if (p.head_dim == 128) LS_TM_CASE(float, float, 128);
+        else LS_TM_CASE(float, float, 64);
+    }
+#undef LS_TM_CASE
     return hipGetLastError();
 }
 

@@ -123,8 +123,8 @@ def test_split_plan_and_workspace_are_stable_and_sane():
     assert length % 64 == 0 and (s - 1) * length < 32768 <= s * length
     assert ls.ls_prefix_split_len(d, 5) % 64 == 0 and ls.ls_prefix_split_len(d, 5) * 5 >= 32768
     n = ls.ls_workspace_bytes(d)
-    parts = (s + 1) * 32 * 64
-    assert n >= parts * 128 * 4 + parts * 4 + 64 * 8 and n % 256 == 0
+    parts = s * 32 * 64
+    assert n >= parts * 128 * 2 + parts * 4 + 64 * 8 and n % 256 == 0
     z = good_desc(p=0)
     assert ls.ls_prefix_num_splits(z) >= 1 and ls.ls_workspace_bytes(z) > 0
     bad = good_desc(); bad.head_dim = 80
@@ -151,11 +151,13 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_build_tree_mask(None, 1, 4, one, None, None) == ls.LS_ERR_NULL
     assert L.ls_build_tree_mask(one, 1, 0, one, None, None) == ls.LS_ERR_SHAPE
     assert L.ls_build_tree_mask(one, 1, 129, one, None, None) == ls.LS_ERR_UNSUPPORTED
-    assert L.ls_prefix_attn_splitkv(dp, one, one, one, None, 0, one, one, None) == ls.LS_ERR_NULL
-    assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, -1, one, one, None) == ls.LS_ERR_SHAPE
+    assert L.ls_prefix_attn_splitkv(dp, one, one, one, None, 0, ls.LS_F32, one, one, None) == ls.LS_ERR_NULL
+    assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, -1, ls.LS_F32, one, one, None) == ls.LS_ERR_SHAPE
+    assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, 2, 5, one, one, None) == ls.LS_ERR_DTYPE
     assert L.ls_tree_attn_masked(dp, one, one, one, None, one, one, None) == ls.LS_ERR_NULL
-    assert L.ls_lse_merge(dp, 0, one, one, one, one, None) == ls.LS_ERR_SHAPE
-    assert L.ls_lse_merge(dp, 2, one, one, None, one, None) == ls.LS_ERR_NULL
+    assert L.ls_lse_merge(dp, 0, ls.LS_F32, one, one, one, one, None) == ls.LS_ERR_SHAPE
+    assert L.ls_lse_merge(dp, 2, ls.LS_F32, one, one, None, one, None) == ls.LS_ERR_NULL
+    assert L.ls_lse_merge(dp, 2, 9, one, one, one, one, None) == ls.LS_ERR_DTYPE
 
 
 def test_binding_raises_when_library_is_missing(tmp_path, monkeypatch):

@@ -111,11 +111,14 @@ def test_tree_attention_alone(dtype, d, t, hq, hkv):
 
 # --------------------------------------------------------------------------- (d) merge ----
 
-@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("f32", 128), ("bf16", 64)])
-def test_merge_alone(dtype, d):
+@pytest.mark.parametrize("dtype,d,parts_bf16", [("f32", 64, False), ("bf16", 128, False), ("f32", 128, False),
+                                                ("bf16", 64, False), ("bf16", 128, True), ("bf16", 64, True)])
+def test_merge_alone(dtype, d, parts_bf16):
     rng = np.random.default_rng(700 + d)
     b, hq, t, parts = 2, 3, 9, 5
     o_parts = rng.standard_normal((b, hq, parts, t, d)).astype(np.float32)
+    if parts_bf16:
+        o_parts = synth.round_to_bf16(o_parts)      # the stored parts are the merge's inputs
     lse_parts = (rng.standard_normal((b, hq, parts, t)) * 4).astype(np.float32)
     lse_parts[0, 0, 1, :] = -np.inf          # an empty part whose output rows hold NaN
     o_parts[0, 0, 1] = np.nan
@@ -125,7 +128,10 @@ def test_merge_alone(dtype, d):
     lse = torch.full((b, hq, t), float("nan"), dtype=torch.float32, device="cuda")
     desc = ls.make_desc(out, None, None, None, None, out, 0)
     desc.n_kv_heads = hq
-    ls.ls_lse_merge(desc, parts, torch.from_numpy(o_parts).cuda(), torch.from_numpy(lse_parts).cuda(), out, lse)
+    dev_parts = torch.from_numpy(o_parts).cuda()
+    if parts_bf16:
+        dev_parts = dev_parts.to(torch.bfloat16)
+    ls.ls_lse_merge(desc, parts, dev_parts, torch.from_numpy(lse_parts).cuda(), out, lse)
     torch.cuda.synchronize()
     ro, rl = oracle.lse_merge(np.moveaxis(o_parts, 2, 3).reshape(-1, parts, d).astype(np.float64),
                               np.moveaxis(lse_parts, 2, 3).reshape(-1, parts).astype(np.float64))
@@ -154,8 +160,11 @@ PREFIX_CASES = [
 ]
 
 
+@pytest.mark.parametrize("parts_bf16", [False, True])
 @pytest.mark.parametrize("dtype,hq,hkv,d,t,plens,n_splits", PREFIX_CASES)
-def test_prefix_splits_alone(dtype, hq, hkv, d, t, plens, n_splits):
+def test_prefix_splits_alone(dtype, hq, hkv, d, t, plens, n_splits, parts_bf16):
+    if parts_bf16 and dtype != "bf16":
+        pytest.skip("bf16 partials go with bf16 problems")
     rng = np.random.default_rng(800 + hq + t)
     seqs = [synth.make_sequence(rng, dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n_tree=t,
                                 prefix_len=p, parents=synth.tree_chain(t), variant="peaked") for p in plens]
@@ -163,12 +172,13 @@ def test_prefix_splits_alone(dtype, hq, hkv, d, t, plens, n_splits):
     db = DeviceBatch(synth.Batch(w, "peaked", seqs))
     s = n_splits or ls.ls_prefix_num_splits(db.desc)
     length = ls.ls_prefix_split_len(db.desc, n_splits)
-    o = torch.full((len(seqs), hq, s, t, d), float("nan"), dtype=torch.float32, device="cuda")
+    o = torch.full((len(seqs), hq, s, t, d), float("nan"), dtype=torch.bfloat16 if parts_bf16 else torch.float32,
+                   device="cuda")
     l = torch.full((len(seqs), hq, s, t), float("nan"), dtype=torch.float32, device="cuda")
-    say(f"prefix-only {dtype} hq={hq} hkv={hkv} d={d} t={t} plens={plens} splits={s} len={length}")
+    say(f"prefix-only parts_bf16={parts_bf16} {dtype} hq={hq} hkv={hkv} d={d} t={t} plens={plens} splits={s} len={length}")
     ls.ls_prefix_attn_splitkv(db.desc, db.q, db.k_cache, db.v_cache, db.prefix_lens, n_splits, o, l)
     torch.cuda.synchronize()
-    o, l = o.cpu().numpy(), l.cpu().numpy()
+    o, l = o.float().cpu().numpy(), l.cpu().numpy()
     for b, sq in enumerate(seqs):
         for k in range(s):
             lo, hi = min(k * length, sq.prefix_len), min((k + 1) * length, sq.prefix_len)
