@@ -119,7 +119,9 @@ Workspace layout(const ls_desc &d, const SplitPlan &plan)
 
 // Split schedule.  The cached keys of every sequence are cut into pieces of split_len rows
 // (a multiple of 64, the MFMA kernel's key tile); the grid is sized for max_prefix_len.
-// Left to the library, the count aims at about one workgroup per compute unit.
+// Left to the library, the count S minimises the modelled time of the cached-key kernel:
+// units*S workgroups run in ceil(units*S / CUs) rounds of max_prefix_len / S keys each, plus
+// a small charge per split for the partial results it adds.
 SplitPlan plan_splits(const ls_desc &d, int32_t request)
 {
     constexpr int kTile = 64;
@@ -132,8 +134,19 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
         const int rows_wg = d.dtype == LS_BF16 ? 256 : 32;
         const int64_t units = (int64_t)d.batch * d.n_kv_heads * ((rows_kv + rows_wg - 1) / rows_wg);
         const int cus = compute_units();
-        s = (cus + units - 1) / units;
-        if (s < 1) s = 1;
+        int64_t s_max = max_p / (4 * kTile);  // at least four key tiles per split
+        if (s_max > 64) s_max = 64;
+        if (s_max < 1) s_max = 1;
+        double best = 0.0;
+        s = 1;
+        for (int64_t cand = 1; cand <= s_max; ++cand) {
+            const int64_t rounds = (units * cand + cus - 1) / cus;
+            const double cost = (double)rounds / (double)cand + 0.0005 * (double)cand;
+            if (cand == 1 || cost < best - 1e-12) {
+                best = cost;
+                s = cand;
+            }
+        }
     }
     int64_t len = (max_p + s - 1) / s;
     len = (len + kTile - 1) / kTile * kTile;

@@ -5,12 +5,13 @@
 // tokens) form one dense query tile, so every cached K/V row is fetched from HBM once per
 // KV head and used by all of them.  A workgroup owns (sequence, KV head, key split, block
 // of up to NW*32 query rows); each of its NW waves owns 32 query rows and all keys.  With
-// NW = 8 two waves share a SIMD, so one wave's softmax arithmetic runs under the other's
-// matrix instructions.
+// NW = 8 two waves share a SIMD.  Each wave runs a software pipeline over 32-key steps whose
+// blocks pair the matrix work of the neighbouring steps (output product of step j-1, score
+// product of step j+1) with the softmax arithmetic of step j.
 //
 // Data movement.  K and V rows go HBM -> LDS directly (global_load_lds_dwordx4, 16 bytes
 // per lane, no staging registers) into a ring of NS stages of 64 keys each, so several
-// tiles are in flight per compute unit while one is consumed.  The instruction writes LDS
+// tiles are in flight per compute unit while two are being consumed.  The instruction writes LDS
 // linearly (lane l -> base + 16*l), so the bank swizzle is applied on the global side:
 // the lane that fills LDS slot (row, pos) fetches chunk pos ^ swizzle(row) of that row.
 //
@@ -38,6 +39,8 @@
 // Only the C/D layout and the pairing of contraction slices between A and B matter.
 // ds_read_b64_tr_b16, per block of 16 lanes: lane L receives element L%4 of the four
 // 8-byte pieces addressed by lanes L/4, L/4+4, L/4+8, L/4+12 of its block.
+#include <type_traits>
+
 #include "ls_internal.hpp"
 
 namespace ls {
@@ -237,27 +240,20 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
         }
     };
 
+    // Tiles requested ahead of the one being consumed: the V half of a tile is still read one
+    // step after its keys were scored (see the pipeline below), so of the NS stages one holds
+    // that tile, one the current tile and PD = NS - 2 are in flight.
+    constexpr int PD = NS - 2;
+    static_assert(PD >= 1 && PD <= 2, "prefetch distance");
     const int n_tiles = (k_hi - k_lo + TK - 1) / TK;
-    const int n_prologue = n_tiles < NS - 1 ? n_tiles : NS - 1;
+    const int n_prologue = n_tiles < PD ? n_tiles : PD;
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
+    for (int s = 0; s < PD; ++s)
         if (s < n_prologue) issue_tile(k_lo + s * TK, s);
 
     // collect Q: everything older than the prologue tiles has landed
-    bool collected = false;
-    if constexpr (NS >= 4) {
-        if (n_prologue >= 3) {
-            wait_vmem<3 * INFLIGHT>();
-            collected = true;
-        }
-    }
-    if constexpr (NS >= 3) {
-        if (!collected && n_prologue == 2) {
-            wait_vmem<2 * INFLIGHT>();
-            collected = true;
-        }
-    }
-    if (!collected) wait_vmem<INFLIGHT>();
+    if (PD >= 2 && n_prologue == 2) wait_vmem<(PD >= 2 ? 2 : 1) * INFLIGHT>();
+    else wait_vmem<INFLIGHT>();
     bf16x8 q_reg[KSTEPS];
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
@@ -288,137 +284,159 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     for (int mt = 0; mt < MT; ++mt)
         v_lane_off[mt] = tr_row * ROWB + (((4 * mt + tr_dchunk) ^ tr_swz) * 16) + tr_sub;
 
-    bool common = false;  // wave-uniform: m_run is set and the common (no max search) path may be tried
-
-    for (int t = 0; t < n_tiles; ++t) {
-        // tile t has landed once at most the younger in-flight tiles remain outstanding
-        const int younger = n_tiles - 1 - t < NS - 2 ? n_tiles - 1 - t : NS - 2;
-        bool waited = false;
-        if constexpr (NS >= 4) {
-            if (younger >= 2) {
-                wait_vmem<2 * INFLIGHT>();
-                waited = true;
+    // ---- building blocks of the pipeline -----------------------------------------------------
+    auto wait_tile = [&](int t) {  // this wave's copies of tile t have landed
+        const int younger = n_tiles - 1 - t < PD - 1 ? n_tiles - 1 - t : PD - 1;
+        if (PD >= 2 && younger >= 1) wait_vmem<(PD >= 2 ? 1 : 0) * INFLIGHT>();
+        else wait_vmem<0>();
+    };
+    auto fetch_k = [&](const uint8_t *ktile, int kt, bf16x8 (&kf)[KSTEPS]) {
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const int pos = (2 * kk + lh) ^ k_swz;
+            kf[kk] = __builtin_bit_cast(bf16x8, *(const uint4 *)(ktile + kt * SUB * ROWB + k_lane_off + pos * 16));
+        }
+    };
+    auto fetch_v = [&](const uint8_t *vtile, int kt, bf16x8 (&vf)[2][MT]) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const uint8_t *vp = vtile + (kt * SUB + a * 16) * ROWB + v_lane_off[mt];
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp));
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp + 8 * ROWB));
+                const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+                vf[a][mt] = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
+            }
+    };
+    auto score = [&](const bf16x8 (&kf)[KSTEPS]) {  // S^T = K Q^T for 32 keys
+        floatx16 s_acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) s_acc = mfma32(kf[kk], q_reg[kk], s_acc);
+        return s_acc;
+    };
+    auto second_product = [&](const bf16x8 (&vf)[2][MT], const uint32_t (&pp)[8]) {  // O^T += V^T P^T
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            const bf16x8 pb =
+                __builtin_bit_cast(bf16x8, make_uint4(pp[4 * a], pp[4 * a + 1], pp[4 * a + 2], pp[4 * a + 3]));
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) o_acc[mt] = mfma32(vf[a][mt], pb, o_acc[mt]);
+        }
+    };
+    auto mask_tail = [&](floatx16 &s_acc, int key0) {  // keys past the end of the split weigh nothing
+        if (key0 + SUB > k_hi) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (key >= k_hi) s_acc[r] = -INFINITY;
             }
         }
-        if constexpr (NS >= 3) {
-            if (!waited && younger == 1) {
-                wait_vmem<INFLIGHT>();
-                waited = true;
-            }
+    };
+    auto numerators = [&](const floatx16 &s_acc, uint32_t (&pp)[8]) {  // with the current m_run
+        const float mc = m_run == -INFINITY ? 0.f : m_run * c;
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(s_acc[r] * c - mc);
+            const float p1 = __builtin_amdgcn_exp2f(s_acc[r + 1] * c - mc);
+            pp[r >> 1] = pack_bf16(p0, p1);
+            sum += p0 + p1;
         }
-        if (!waited) wait_vmem<0>();
-        __syncthreads();  // every wave's part of tile t is in LDS; every wave is done with tile t-1
-        if (t + NS - 1 < n_tiles) issue_tile(k_lo + (t + NS - 1) * TK, (t + NS - 1) % NS);
+        return sum;
+    };
+    auto raise_reference = [&](const floatx16 &s_acc) {  // general path: lift m_run, rescale O and l
+        float mx = s_acc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_acc[r]);
+        mx = half_max(mx);
+        const bool grow = (mx - m_run) * c > kLazy;  // also true while m_run is -inf
+        if (__any(grow)) {
+            const float m_new = fmaxf(m_run, mx);
+            // a step whose keys are all masked leaves m_new = -inf; keep arithmetic finite
+            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * c);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[mt][r] *= alpha;
+        }
+    };
 
+    // ---- software pipeline over 32-key steps --------------------------------------------------
+    // Step j scores keys, turns scores into numerators and adds their weighted values to O.
+    // One pipeline block handles three independent pieces of neighbouring steps: the output
+    // product of step j-1 (matrix core), the softmax arithmetic of step j (vector ALU) and the
+    // score product of step j+1 (matrix core).  Every block thus carries 16 matrix instructions
+    // next to its vector work, for this wave and for the one sharing its SIMD alike.
+    bf16x8 k_frag[KSTEPS];
+    bf16x8 v_frag[2][MT];
+    uint32_t p_prev[8];
+    floatx16 s_cur;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) v_frag[a][mt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 8; ++r) p_prev[r] = 0;  // the first block's output product adds zero
+
+    wait_tile(0);
+    __syncthreads();
+    if (PD < n_tiles) issue_tile(k_lo + PD * TK, PD % NS);
+    fetch_k(smem, 0, k_frag);
+    s_cur = score(k_frag);
+    mask_tail(s_cur, k_lo);
+    raise_reference(s_cur);  // sets m_run from the first 32 keys (at least one of them is valid)
+
+    // one block: consumes s_cur / p_prev / v_frag, leaves the next step's in their place
+    auto block = [&](auto has_next_tag, const uint8_t *k_next, int kt_next, const uint8_t *v_cur, int kt_cur,
+                     int key0_next) {
+        constexpr bool has_next = decltype(has_next_tag)::value;
+        if constexpr (has_next) fetch_k(k_next, kt_next, k_frag);
+        second_product(v_frag, p_prev);
+        uint32_t p_cur[8];
+        float sum = numerators(s_cur, p_cur);
+        floatx16 s_next = s_cur;
+        if constexpr (has_next) s_next = score(k_frag);
+        fetch_v(v_cur, kt_cur, v_frag);
+        if (__any(!(sum < kSumCap))) {  // also catches inf and nan: redo this step on the general path
+            raise_reference(s_cur);
+            sum = numerators(s_cur, p_cur);
+        }
+        l_run += sum;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) p_prev[r] = p_cur[r];
+        if constexpr (has_next) mask_tail(s_next, key0_next);
+        s_cur = s_next;
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+
+    for (int t = 0; t + 1 < n_tiles; ++t) {
         const uint8_t *ks = smem + (t % NS) * STAGEB;
         const uint8_t *vs = ks + TILEB;
         const int k0 = k_lo + t * TK;
-
-        // Operand fragments are fetched from LDS a step ahead of the matrix instructions that
-        // use them: K for step 0 right after the barrier, then inside step kt the V fragments of
-        // kt and the K fragments of kt+1 are requested before the softmax arithmetic so that
-        // they land under it.
-        bf16x8 k_frag[KSTEPS];
-        auto fetch_k = [&](int kt) {
-#pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) {
-                const int pos = (2 * kk + lh) ^ k_swz;
-                k_frag[kk] =
-                    __builtin_bit_cast(bf16x8, *(const uint4 *)(ks + kt * SUB * ROWB + k_lane_off + pos * 16));
-            }
-        };
-        fetch_k(0);
-
-#pragma unroll
-        for (int kt = 0; kt < TK / SUB; ++kt) {
-            // ---- S^T = K Q^T for 32 keys --------------------------------------------------
-            floatx16 s_acc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) s_acc = mfma32(k_frag[kk], q_reg[kk], s_acc);
-            __builtin_amdgcn_sched_barrier(0);
-
-            bf16x8 v_frag[2][MT];
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const uint8_t *vp = vs + (kt * SUB + a * 16) * ROWB + v_lane_off[mt];
-                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp));
-                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp + 8 * ROWB));
-                    const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
-                    v_frag[a][mt] = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
-                }
-            if (kt + 1 < TK / SUB) fetch_k(kt + 1);
-            __builtin_amdgcn_sched_barrier(0);
-
-            // keys past the end of the split weigh nothing (only the last tile can hold any)
-            if (k0 + (kt + 1) * SUB > k_hi) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = k0 + kt * SUB + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    if (key >= k_hi) s_acc[r] = -INFINITY;
-                }
-            }
-
-            // ---- softmax numerators, one query per lane -----------------------------------
-            uint32_t p_pk[8];  // bf16 pairs: the B operand of the second product
-            float sum = 0.f;
-            bool done = false;
-            if (common) {
-                const float mc = m_run * c;
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(s_acc[r] * c - mc);
-                    const float p1 = __builtin_amdgcn_exp2f(s_acc[r + 1] * c - mc);
-                    p_pk[r >> 1] = pack_bf16(p0, p1);
-                    sum += p0 + p1;
-                }
-                done = !__any(!(sum < kSumCap));  // also catches inf and nan
-            }
-            if (!done) {
-                float mx = s_acc[0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_acc[r]);
-                mx = half_max(mx);
-                const bool grow = (mx - m_run) * c > kLazy;  // also true while m_run is -inf
-                if (__any(grow)) {
-                    const float m_new = fmaxf(m_run, mx);
-                    // a step whose keys are all masked leaves m_new = -inf; keep arithmetic finite
-                    const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * c);
-                    m_run = m_new;
-                    l_run *= alpha;
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) o_acc[mt][r] *= alpha;
-                }
-                const float mc = m_run == -INFINITY ? 0.f : m_run * c;
-                sum = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(s_acc[r] * c - mc);
-                    const float p1 = __builtin_amdgcn_exp2f(s_acc[r + 1] * c - mc);
-                    p_pk[r >> 1] = pack_bf16(p0, p1);
-                    sum += p0 + p1;
-                }
-                common = !__any(m_run == -INFINITY);
-            }
-            l_run += sum;
-
-            // ---- O^T += V^T P^T ---------------------------------------------------------
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                const bf16x8 pb = __builtin_bit_cast(
-                    bf16x8, make_uint4(p_pk[4 * a], p_pk[4 * a + 1], p_pk[4 * a + 2], p_pk[4 * a + 3]));
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) o_acc[mt] = mfma32(v_frag[a][mt], pb, o_acc[mt]);
-            }
-        }
+        // first half of tile t: the next step is the second half of the same tile
+        block(yes{}, ks, 1, vs, 0, k0 + SUB);
+        // second half: the next step opens tile t+1, which needs the barrier
+        wait_tile(t + 1);
+        __syncthreads();  // tile t+1 is complete in LDS; nobody reads tile t-1 any more
+        if (t + 1 + PD < n_tiles) issue_tile(k_lo + (t + 1 + PD) * TK, (t + 1 + PD) % NS);
+        block(yes{}, smem + ((t + 1) % NS) * STAGEB, 0, vs, 1, k0 + TK);
     }
+    {  // the last tile: its second half has no successor
+        const int t = n_tiles - 1;
+        const uint8_t *ks = smem + (t % NS) * STAGEB;
+        const uint8_t *vs = ks + TILEB;
+        block(yes{}, ks, 1, vs, 0, k_lo + t * TK + SUB);
+        block(no{}, ks, 0, vs, 1, 0);
+    }
+    second_product(v_frag, p_prev);  // the output product of the last step
 
     // ---- epilogue: normalise and store this split's partial result -----------------------
     const float l_tot = half_sum(l_run);

@@ -223,12 +223,47 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
+// Raw (unconverted) pieces, so that many loads can be in flight before the first is used.
+template <typename PT, int EPL> struct Raw;
+template <> struct Raw<float, 1> {
+    typedef float type;
+    static __device__ __forceinline__ type load(const float *p) { return *p; }
+    static __device__ __forceinline__ void unpack(type r, float *v) { v[0] = r; }
+};
+template <> struct Raw<float, 2> {
+    typedef float2 type;
+    static __device__ __forceinline__ type load(const float *p) { return *(const float2 *)p; }
+    static __device__ __forceinline__ void unpack(type r, float *v)
+    {
+        v[0] = r.x;
+        v[1] = r.y;
+    }
+};
+template <> struct Raw<uint16_t, 1> {
+    typedef uint16_t type;
+    static __device__ __forceinline__ type load(const uint16_t *p) { return *p; }
+    static __device__ __forceinline__ void unpack(type r, float *v) { v[0] = bf16_to_float(r); }
+};
+template <> struct Raw<uint16_t, 2> {
+    typedef uint32_t type;
+    static __device__ __forceinline__ type load(const uint16_t *p) { return *(const uint32_t *)p; }
+    static __device__ __forceinline__ void unpack(type r, float *v)
+    {
+        v[0] = __uint_as_float(r << 16);
+        v[1] = __uint_as_float(r & 0xffff0000u);
+    }
+};
+
 template <typename T, typename PT, int D>
 __global__ void __launch_bounds__(256)
 tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, int32_t n_cache, T *__restrict__ out,
                   int64_t os0, int64_t os1, int64_t os2, float *__restrict__ lse)
 {
     constexpr int EPL = D / kWave;
+    constexpr int CHUNK = 32;  // split rows requested before any is used
+    constexpr int KB = 4;      // tree keys requested together
+    typedef Raw<PT, EPL> RP;
+    typedef Raw<T, EPL> RT;
     const int lane = threadIdx.x & (kWave - 1);
     const int row = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
     const int rows_total = p.batch * p.n_q_heads * p.n_tree;
@@ -239,19 +274,27 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
     const int g = h / p.group;
     const int words = (p.n_tree + 63) >> 6;
 
-    // part weights first, so that their loads are in flight during the tree part
     const size_t prow0 = (((size_t)b * p.n_q_heads + h) * parts.parts_stride + parts.part_base) * p.n_tree + i;
     const float *lp = parts.lse + prow0;
     const PT *op = (const PT *)parts.o + prow0 * D + lane * EPL;
     const size_t part_step = (size_t)p.n_tree * D;  // elements between consecutive parts of one row
 
+    // Requests first: the first 64 part LSEs (one per lane) and the first CHUNK split rows.
+    const float l_first = lane < n_cache ? lp[(size_t)lane * p.n_tree] : -INFINITY;
+    typename RP::type raw[CHUNK];
+#pragma unroll
+    for (int k = 0; k < CHUNK; ++k) {
+        const int part = k < n_cache ? k : (n_cache > 0 ? n_cache - 1 : 0);  // clamped: always a valid row
+        if (n_cache > 0) raw[k] = RP::load(op + (size_t)part * part_step);
+    }
+
     // ---- masked attention over the tree keys (unnormalised, base-2 logits) ----------------
     const T *qrow = (const T *)p.q + b * p.q_stride[0] + h * p.q_stride[1] + i * p.q_stride[2];
-    const T *kbase = (const T *)p.k_tree + b * p.kt_stride[0] + g * p.kt_stride[1];
-    const T *vbase = (const T *)p.v_tree + b * p.vt_stride[0] + g * p.vt_stride[1];
+    const T *kbase = (const T *)p.k_tree + b * p.kt_stride[0] + g * p.kt_stride[1] + lane * EPL;
+    const T *vbase = (const T *)p.v_tree + b * p.vt_stride[0] + g * p.vt_stride[1] + lane * EPL;
     const uint64_t *mrow = mask + ((size_t)b * p.n_tree + i) * words;
     float qv[EPL], acc[EPL];
-    Piece<EPL>::load(qrow + lane * EPL, qv);
+    RT::unpack(RT::load(qrow + lane * EPL), qv);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
         qv[e] *= p.scale_log2;
@@ -262,29 +305,42 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
         uint64_t bits = mrow[w];
         if (w == words - 1 && (p.n_tree & 63)) bits &= ((uint64_t)1 << (p.n_tree & 63)) - 1;
         while (bits) {
-            const int j = (w << 6) + __builtin_ctzll(bits);
-            bits &= bits - 1;
-            float kv[EPL], vv[EPL];
-            Piece<EPL>::load(kbase + j * p.kt_stride[2] + lane * EPL, kv);
-            Piece<EPL>::load(vbase + j * p.vt_stride[2] + lane * EPL, vv);
-            float part = 0.f;
+            // up to KB visible keys at a time, all their rows requested before the first is used
+            int idx[KB];
+            typename RT::type kr[KB], vr[KB];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) part += qv[e] * kv[e];
-            const float z = wave_sum(part);
-            const float m_new = fmaxf(m_run, z);
-            const float alpha = exp2f(m_run - m_new);
-            const float pj = exp2f(z - m_new);
-            l_run = l_run * alpha + pj;
+            for (int u = 0; u < KB; ++u) {
+                idx[u] = bits ? (w << 6) + __builtin_ctzll(bits) : -1;
+                bits &= bits - 1;  // 0 stays 0
+                const int j = idx[u] < 0 ? 0 : idx[u];
+                kr[u] = RT::load(kbase + j * p.kt_stride[2]);
+                vr[u] = RT::load(vbase + j * p.vt_stride[2]);
+            }
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * alpha + pj * vv[e];
-            m_run = m_new;
+            for (int u = 0; u < KB; ++u) {
+                if (idx[u] < 0) break;  // wave-uniform
+                float kv[EPL], vv[EPL];
+                RT::unpack(kr[u], kv);
+                RT::unpack(vr[u], vv);
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) part += qv[e] * kv[e];
+                const float z = wave_sum(part);
+                const float m_new = fmaxf(m_run, z);
+                const float alpha = exp2f(m_run - m_new);
+                const float pj = exp2f(z - m_new);
+                l_run = l_run * alpha + pj;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * alpha + pj * vv[e];
+                m_run = m_new;
+            }
         }
     }
     const float lse_tree = l_run > 0.f ? (m_run + log2f(l_run)) * kLn2 : -INFINITY;
 
     // ---- merge --------------------------------------------------------------------------
-    float top = lse_tree;
-    for (int s0 = 0; s0 < n_cache; s0 += kWave) {
+    float top = fmaxf(lse_tree, wave_max(l_first));
+    for (int s0 = kWave; s0 < n_cache; s0 += kWave) {
         const int s = s0 + lane;
         const float l = s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY;
         top = fmaxf(top, wave_max(l));
@@ -302,24 +358,31 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
     const float tree_scale = l_run > 0.f ? w_tree / l_run : 0.f;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) o[e] = acc[e] * tree_scale;
-    float w_lane = 0.f;  // this lane's part weights, summed over the 64-part chunks
+    float w_lane = 0.f;  // this lane's part weights, summed over the 64-part groups
     for (int s0 = 0; s0 < n_cache; s0 += kWave) {
         const int s = s0 + lane;
-        const float l = s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY;
+        const float l = s0 == 0 ? l_first : (s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY);
         const float w = l == -INFINITY ? 0.f : exp2f((l - top) * kLog2e);
         w_lane += w;
         const int cnt = n_cache - s0 < kWave ? n_cache - s0 : kWave;
-        for (int k8 = 0; k8 < cnt; k8 += 8) {
+        for (int c0 = 0; c0 < cnt; c0 += CHUNK) {
+            if (s0 + c0 > 0) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                // past the last part the lane weight is 0 and the (clamped) address is still valid
-                const int k = k8 + u;
-                const int part = s0 + k < n_cache ? s0 + k : n_cache - 1;
-                const float wk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), k));
+                for (int k = 0; k < CHUNK; ++k) {
+                    const int part = s0 + c0 + k < n_cache ? s0 + c0 + k : n_cache - 1;
+                    raw[k] = RP::load(op + (size_t)part * part_step);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < CHUNK; ++k) {
+                // past the last part the lane weight is 0 (the clamped row was still a valid read);
+                // empty parts may hold anything, so they are selected out rather than multiplied
+                const float wk =
+                    __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), c0 + k));
                 float v[EPL];
-                Piece<EPL>::load(op + (size_t)part * part_step, v);
+                RP::unpack(raw[k], v);
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) o[e] += wk > 0.f ? wk * v[e] : 0.f;  // empty parts may hold anything
+                for (int e = 0; e < EPL; ++e) o[e] += wk > 0.f ? wk * v[e] : 0.f;
             }
         }
     }
