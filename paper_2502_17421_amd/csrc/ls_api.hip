@@ -134,7 +134,8 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
         const int rows_wg = d.dtype == LS_BF16 ? 256 : 32;
         const int64_t units = (int64_t)d.batch * d.n_kv_heads * ((rows_kv + rows_wg - 1) / rows_wg);
         const int cus = compute_units();
-        int64_t s_max = max_p / (4 * kTile);  // at least four key tiles per split
+        // at least four key tiles per split on the MFMA path; the float path has 32-key tiles
+        int64_t s_max = max_p / (d.dtype == LS_BF16 ? 4 * kTile : kTile);
         if (s_max > 64) s_max = 64;
         if (s_max < 1) s_max = 1;
         double best = 0.0;

@@ -14,6 +14,14 @@ namespace ls {
 namespace {
 constexpr int TQ = 32;  // query rows per workgroup
 constexpr int TK = 32;  // keys per tile
+
+__device__ __forceinline__ float4 load4(const float *p) { return *(const float4 *)p; }
+__device__ __forceinline__ float4 load4(const uint16_t *p)
+{
+    const uint2 v = *(const uint2 *)p;
+    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                       __uint_as_float(v.y & 0xffff0000u));
+}
 }
 
 template <typename T, int D>
@@ -21,9 +29,9 @@ __global__ void __launch_bounds__(256)
 prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
 {
     constexpr int KP = D + 1;  // padded key row: threads c = 0..7 hit distinct banks
-    __shared__ float q_s[TQ][D];
+    __shared__ float q_s[TQ][KP];  // padded like k_s: the 8 rows a wave reads together hit distinct banks
     __shared__ float k_s[TK][KP];
-    __shared__ float v_s[TK][D];
+    __shared__ __attribute__((aligned(16))) float v_s[TK][D];
     __shared__ float p_s[TQ][TK + 1];
 
     const int tid = threadIdx.x;
@@ -46,17 +54,32 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
     const int hq = g * p.group + (row_ok ? m / p.n_tree : 0);
     const int ti = row_ok ? m % p.n_tree : 0;
 
-    // stage the query block, pre-multiplied by scale*log2(e)
-    for (int e = tid; e < TQ * D; e += 256) {
-        const int rr = e / D, dd = e % D;
-        const int mm = qblock * TQ + rr;
-        float v = 0.f;
-        if (mm < rows_kv) {
-            const T *qp = (const T *)p.q + b * p.q_stride[0] + (g * p.group + mm / p.n_tree) * p.q_stride[1] +
-                          (mm % p.n_tree) * p.q_stride[2];
-            v = Elem<T>::load(qp + dd) * p.scale_log2;
+    // stage the query block, pre-multiplied by scale*log2(e); 4 consecutive elements per thread
+    // and step, all loads of a thread issued before the first LDS store
+    constexpr int QV = TQ * D / 4 / 256;  // 4-element pieces per thread
+    {
+        float4 qv[QV];
+#pragma unroll
+        for (int n = 0; n < QV; ++n) {
+            const int e = (tid + n * 256) * 4;
+            const int rr = e / D, dd = e % D;
+            const int mm = qblock * TQ + rr;
+            qv[n] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (mm < rows_kv) {
+                const T *qp = (const T *)p.q + b * p.q_stride[0] + (g * p.group + mm / p.n_tree) * p.q_stride[1] +
+                              (mm % p.n_tree) * p.q_stride[2];
+                qv[n] = load4(qp + dd);
+            }
         }
-        q_s[rr][dd] = v;
+#pragma unroll
+        for (int n = 0; n < QV; ++n) {
+            const int e = (tid + n * 256) * 4;
+            const int rr = e / D, dd = e % D;
+            q_s[rr][dd + 0] = qv[n].x * p.scale_log2;
+            q_s[rr][dd + 1] = qv[n].y * p.scale_log2;
+            q_s[rr][dd + 2] = qv[n].z * p.scale_log2;
+            q_s[rr][dd + 3] = qv[n].w * p.scale_log2;
+        }
     }
 
     float acc[D / 8];
@@ -69,16 +92,31 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
 
     for (int k0 = k_lo; k0 < k_hi; k0 += TK) {
         __syncthreads();  // previous tile fully consumed (and q_s visible on the first pass)
-        for (int e = tid; e < TK * D; e += 256) {
-            const int jj = e / D, dd = e % D;
-            const int key = k0 + jj;
-            float kv = 0.f, vv = 0.f;
-            if (key < k_hi) {
-                kv = Elem<T>::load(kbase + key * p.kc_stride[2] + dd);
-                vv = Elem<T>::load(vbase + key * p.vc_stride[2] + dd);
+        {
+            constexpr int KV = TK * D / 4 / 256;  // 4-element pieces per thread and tensor
+            float4 kr[KV], vr[KV];
+#pragma unroll
+            for (int n = 0; n < KV; ++n) {
+                const int e = (tid + n * 256) * 4;
+                const int jj = e / D, dd = e % D;
+                const int key = k0 + jj;
+                kr[n] = make_float4(0.f, 0.f, 0.f, 0.f);
+                vr[n] = kr[n];
+                if (key < k_hi) {
+                    kr[n] = load4(kbase + key * p.kc_stride[2] + dd);
+                    vr[n] = load4(vbase + key * p.vc_stride[2] + dd);
+                }
             }
-            k_s[jj][dd] = kv;
-            v_s[jj][dd] = vv;
+#pragma unroll
+            for (int n = 0; n < KV; ++n) {
+                const int e = (tid + n * 256) * 4;
+                const int jj = e / D, dd = e % D;
+                k_s[jj][dd + 0] = kr[n].x;
+                k_s[jj][dd + 1] = kr[n].y;
+                k_s[jj][dd + 2] = kr[n].z;
+                k_s[jj][dd + 3] = kr[n].w;
+                *(float4 *)&v_s[jj][dd] = vr[n];
+            }
         }
         __syncthreads();
 

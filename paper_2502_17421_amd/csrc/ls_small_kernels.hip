@@ -254,14 +254,14 @@ template <> struct Raw<uint16_t, 2> {
     }
 };
 
-template <typename T, typename PT, int D>
+template <typename T, typename PT, int D, int CHUNK>
 __global__ void __launch_bounds__(256)
 tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, int32_t n_cache, T *__restrict__ out,
                   int64_t os0, int64_t os1, int64_t os2, float *__restrict__ lse)
 {
     constexpr int EPL = D / kWave;
-    constexpr int CHUNK = 32;  // split rows requested before any is used
-    constexpr int KB = 4;      // tree keys requested together
+    // CHUNK: split rows requested before any is used
+    constexpr int KB = 8;  // tree keys requested together
     typedef Raw<PT, EPL> RP;
     typedef Raw<T, EPL> RT;
     const int lane = threadIdx.x & (kWave - 1);
@@ -400,9 +400,14 @@ hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, 
 {
     const int rows = p.batch * p.n_q_heads * p.n_tree;
     const dim3 block(256), grid((rows + 3) / 4);
-#define LS_TM_CASE(T, PT, DD)                                                                                  \
-    hipLaunchKernelGGL((tree_merge_kernel<T, PT, DD>), grid, block, 0, stream, p, mask, cache_parts, n_cache_parts, \
-                       (T *)out, o_stride[0], o_stride[1], o_stride[2], lse)
+#define LS_TM_LAUNCH(T, PT, DD, CH)                                                                          \
+    hipLaunchKernelGGL((tree_merge_kernel<T, PT, DD, CH>), grid, block, 0, stream, p, mask, cache_parts,      \
+                       n_cache_parts, (T *)out, o_stride[0], o_stride[1], o_stride[2], lse)
+#define LS_TM_CASE(T, PT, DD)                          \
+    do {                                               \
+        if (n_cache_parts <= 8) LS_TM_LAUNCH(T, PT, DD, 8); \
+        else LS_TM_LAUNCH(T, PT, DD, 32);              \
+    } while (0)
     if (p.head_dim != 64 && p.head_dim != 128) return hipErrorInvalidValue;
     if (dtype == LS_BF16) {
         if (cache_parts.o_is_bf16) {
@@ -418,6 +423,7 @@ hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, 
         else LS_TM_CASE(float, float, 64);
     }
 #undef LS_TM_CASE
+#undef LS_TM_LAUNCH
     return hipGetLastError();
 }
 
