@@ -233,6 +233,31 @@ def test_full_path_ragged_batch(variant):
     assert err >= db.workspace.data_ptr()
 
 
+@pytest.mark.parametrize("dtype,hq,hkv,d,t,plens", [
+    ("bf16", 8, 2, 64, 24, [1300]),          # head_dim 64 through the whole path
+    ("f32", 6, 2, 128, 9, [700, 333]),       # float problem with head_dim 128, two sequences
+    ("bf16", 4, 4, 128, 1, [900]),           # a single tree token: plain decode attention
+    ("bf16", 14, 2, 128, 100, [2000]),       # 700 rows per KV head, two mask words
+    ("bf16", 2, 1, 128, 128, [64, 4100, 1]),  # largest tree, very different lengths
+    ("f32", 2, 2, 64, 128, [100]),
+])
+def test_full_path_other_shapes(dtype, hq, hkv, d, t, plens):
+    rng = np.random.default_rng(900 + hq + t)
+    seqs = []
+    for pl in plens:
+        parents = synth.tree_constrained(rng, t, 10, 4) if t > 1 else np.asarray([-1], dtype=np.int32)
+        seqs.append(synth.make_sequence(rng, dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n_tree=t,
+                                        prefix_len=pl, parents=parents, variant="peaked"))
+    w = synth.Workload("case", dtype, len(seqs), hq, hkv, d, t, min(plens), max(plens), None, None, 0)
+    batch = synth.Batch(w, "peaked", seqs)
+    db = DeviceBatch(batch)
+    say(f"whole path {dtype} hq={hq} hkv={hkv} d={d} t={t} plens={plens} splits={ls.ls_prefix_num_splits(db.desc)}")
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, dtype, "  result", stress=True))
+
+
 def test_full_path_token_major_layout():
     batch = small("C2", 1300, "peaked")
     db = DeviceBatch(batch, token_major=True)
