@@ -337,6 +337,101 @@ def test_bad_parents_on_device_set_the_error_word():
     assert torch.isfinite(db.out.float()).all()
 
 
+# ------------------------------------------------ properties that hold at any size ----
+
+def _prefix_then_merge(db, n_splits, part_dtype):
+    """ls_prefix_attn_splitkv with a chosen split count + ls_tree_attn_masked + ls_lse_merge: the
+    path assembled from its stand-alone subsystems (three more launches than the fused call)."""
+    w = db.batch.workload
+    b, hq, t, d = db.q.shape
+    o = torch.zeros((b, hq, n_splits + 1, t, d), dtype=torch.float32, device="cuda")
+    l = torch.full((b, hq, n_splits + 1, t), float("-inf"), dtype=torch.float32, device="cuda")
+    op = torch.empty((b, hq, n_splits, t, d), dtype=part_dtype, device="cuda")
+    lp = torch.empty((b, hq, n_splits, t), dtype=torch.float32, device="cuda")
+    ls.ls_prefix_attn_splitkv(db.desc, db.q, db.k_cache, db.v_cache, db.prefix_lens, n_splits, op, lp)
+    words = (t + 63) // 64
+    mask = torch.zeros((b, t, words), dtype=torch.int64, device="cuda")
+    ls.ls_build_tree_mask(db.parents, mask)
+    ot = torch.empty((b, hq, t, d), dtype=torch.float32, device="cuda")
+    lt = torch.empty((b, hq, t), dtype=torch.float32, device="cuda")
+    ls.ls_tree_attn_masked(db.desc, db.q, db.k_tree, db.v_tree, mask, ot, lt)
+    o[:, :, :n_splits] = torch.nan_to_num(op.float(), nan=0.0)      # empty splits hold whatever was there
+    l[:, :, :n_splits] = lp
+    o[:, :, n_splits] = ot
+    l[:, :, n_splits] = lt
+    out = torch.empty_like(db.out)
+    lse = torch.empty_like(db.lse)
+    ls.ls_lse_merge(db.desc, n_splits + 1, o, l, out, lse)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), lse.cpu().numpy()
+
+
+@pytest.mark.parametrize("name,prefix", [("C2", 2300), ("C4", 1500), ("C1", 1024)])
+def test_split_count_does_not_matter(name, prefix):
+    """The appendix proposition on the device: any number of key splits, assembled from the
+    stand-alone subsystems, gives the same result as the fused call (and as the oracle)."""
+    batch = small(name, prefix, "peaked")
+    w = batch.workload
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    base_o, base_l = out.float().cpu().numpy(), lse.cpu().numpy()
+    ro, rl = oracle_full(batch)
+    tol = 2e-2 if w.dtype == "bf16" else 1e-5
+    for n_splits in (1, 3, 7):
+        o, l = _prefix_then_merge(db, n_splits, torch.float32)
+        say(gates(o, l, ro, rl, w.dtype, f"{name} assembled, {n_splits} splits, float parts", stress=True))
+        assert np.abs(o - base_o).max() <= tol * max(1.0, np.abs(ro).max())
+        assert np.abs(l - base_l).max() <= (2e-3 if w.dtype == "bf16" else 2e-5)
+    if w.dtype == "bf16":
+        o, l = _prefix_then_merge(db, 5, torch.bfloat16)
+        say(gates(o, l, ro, rl, w.dtype, f"{name} assembled, 5 splits, bf16 parts", stress=True))
+
+
+def test_permuting_cached_rows_on_device():
+    """Reordering the cached rows (K and V together) changes tile and split membership of every
+    key but not the result beyond rounding."""
+    batch = small("C2", 1900, "peaked")
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    o1, l1 = out.float().cpu().numpy().copy(), lse.cpu().numpy().copy()
+    perm = torch.randperm(1900, device="cuda", generator=torch.Generator(device="cuda").manual_seed(5))
+    db.k_cache.copy_(db.k_cache[:, :, perm].clone())
+    db.v_cache.copy_(db.v_cache[:, :, perm].clone())
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    o2, l2 = out.float().cpu().numpy(), lse.cpu().numpy()
+    assert np.abs(l2 - l1).max() < 1e-4
+    assert np.abs(o2 - o1).max() <= 2e-2 * np.abs(o1).max()
+    assert np.sqrt(((o2 - o1) ** 2).mean()) <= 5e-3 * np.sqrt((o1 ** 2).mean())
+
+
+def test_scale_override_and_group_mapping():
+    """softmax_scale from the descriptor is honoured, and query head h reads KV head h // G:
+    with distinct KV heads, shuffling KV heads changes the result unless the query heads move too."""
+    batch = small("C2", 800, "peaked")
+    db = DeviceBatch(batch)
+    db.desc.softmax_scale = 0.05
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch, scale=0.05)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", "C2 scale 0.05", stress=True))
+    g = batch.workload.group
+    hkv = batch.workload.n_kv_heads
+    perm = torch.tensor([3, 0, 1, 2, 5, 4, 7, 6], device="cuda")
+    qperm = (perm[:, None] * g + torch.arange(g, device="cuda")[None, :]).reshape(-1)
+    db2 = DeviceBatch(batch)
+    db2.desc.softmax_scale = 0.05
+    for name in ("k_cache", "v_cache", "k_tree", "v_tree"):
+        getattr(db2, name).copy_(getattr(db2, name)[:, perm].clone())
+    db2.q.copy_(db2.q[:, qperm].clone())
+    out2, lse2 = db2.run_full()
+    torch.cuda.synchronize()
+    assert torch.equal(out2.view(torch.int16), out[:, qperm].view(torch.int16)), "head grouping"
+    assert hkv == 8
+
+
 # ------------------------------------------------ the benchmark shapes at full size ----
 
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
