@@ -6,7 +6,7 @@
 // rows of a KV head are the G*T rows (g, t) of its G query heads.  Keys are streamed in
 // tiles of 32 through LDS; scores, the online softmax and the P*V product are computed per
 // tile.  Thread (r, c) = (tid / 8, tid % 8) owns query row r: it computes the scores of
-// keys c, c+8, c+16, c+24 of the tile and accumulates output columns c, c+8, ...
+// keys c, c+8, c+16, c+24 of the tile and accumulates output columns 4(c+8i) .. 4(c+8i)+3.
 #include "ls_internal.hpp"
 
 namespace ls {
@@ -28,11 +28,11 @@ template <typename T, int D>
 __global__ void __launch_bounds__(256)
 prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
 {
-    constexpr int KP = D + 1;  // padded key row: threads c = 0..7 hit distinct banks
-    __shared__ float q_s[TQ][KP];  // padded like k_s: the 8 rows a wave reads together hit distinct banks
-    __shared__ float k_s[TK][KP];
+    constexpr int KP = D + 4;  // padded row, still 16-byte aligned: the 8 rows a wave reads together hit distinct banks
+    __shared__ __attribute__((aligned(16))) float q_s[TQ][KP];
+    __shared__ __attribute__((aligned(16))) float k_s[TK][KP];
     __shared__ __attribute__((aligned(16))) float v_s[TK][D];
-    __shared__ float p_s[TQ][TK + 1];
+    __shared__ __attribute__((aligned(16))) float p_s[TQ][TK + 4];
 
     const int tid = threadIdx.x;
     const int r = tid >> 3, c = tid & 7;
@@ -75,16 +75,15 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
         for (int n = 0; n < QV; ++n) {
             const int e = (tid + n * 256) * 4;
             const int rr = e / D, dd = e % D;
-            q_s[rr][dd + 0] = qv[n].x * p.scale_log2;
-            q_s[rr][dd + 1] = qv[n].y * p.scale_log2;
-            q_s[rr][dd + 2] = qv[n].z * p.scale_log2;
-            q_s[rr][dd + 3] = qv[n].w * p.scale_log2;
+            *(float4 *)&q_s[rr][dd] = make_float4(qv[n].x * p.scale_log2, qv[n].y * p.scale_log2,
+                                                  qv[n].z * p.scale_log2, qv[n].w * p.scale_log2);
         }
     }
 
-    float acc[D / 8];
+    // thread (r, c) accumulates output columns 4*(c + 8*i) .. +3 of row r, i < D/32
+    float4 acc[D / 32];
 #pragma unroll
-    for (int k = 0; k < D / 8; ++k) acc[k] = 0.f;
+    for (int i = 0; i < D / 32; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     float m_run = -INFINITY, l_run = 0.f;
 
     const T *kbase = (const T *)p.k_cache + b * p.kc_stride[0] + g * p.kc_stride[1];
@@ -111,10 +110,7 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
             for (int n = 0; n < KV; ++n) {
                 const int e = (tid + n * 256) * 4;
                 const int jj = e / D, dd = e % D;
-                k_s[jj][dd + 0] = kr[n].x;
-                k_s[jj][dd + 1] = kr[n].y;
-                k_s[jj][dd + 2] = kr[n].z;
-                k_s[jj][dd + 3] = kr[n].w;
+                *(float4 *)&k_s[jj][dd] = kr[n];
                 *(float4 *)&v_s[jj][dd] = vr[n];
             }
         }
@@ -123,10 +119,14 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
         float s[4];
 #pragma unroll
         for (int a = 0; a < 4; ++a) s[a] = 0.f;
-        for (int dd = 0; dd < D; ++dd) {
-            const float qd = q_s[r][dd];
+#pragma unroll 4
+        for (int dd = 0; dd < D; dd += 4) {
+            const float4 q4 = *(const float4 *)&q_s[r][dd];
 #pragma unroll
-            for (int a = 0; a < 4; ++a) s[a] += qd * k_s[c + 8 * a][dd];
+            for (int a = 0; a < 4; ++a) {
+                const float4 k4 = *(const float4 *)&k_s[c + 8 * a][dd];
+                s[a] += q4.x * k4.x + q4.y * k4.y + q4.z * k4.z + q4.w * k4.w;
+            }
         }
         float tmax = -INFINITY;
 #pragma unroll
@@ -150,12 +150,27 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
         l_run = l_run * alpha + psum;
         m_run = m_new;
 #pragma unroll
-        for (int k = 0; k < D / 8; ++k) acc[k] *= alpha;
+        for (int i = 0; i < D / 32; ++i) {
+            acc[i].x *= alpha;
+            acc[i].y *= alpha;
+            acc[i].z *= alpha;
+            acc[i].w *= alpha;
+        }
         __syncthreads();  // p_s row r complete
-        for (int jj = 0; jj < TK; ++jj) {
-            const float pj = p_s[r][jj];
+#pragma unroll 2
+        for (int jj = 0; jj < TK; jj += 4) {
+            const float4 p4 = *(const float4 *)&p_s[r][jj];
+            const float pj[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
-            for (int k = 0; k < D / 8; ++k) acc[k] += pj * v_s[jj][c + 8 * k];
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < D / 32; ++i) {
+                    const float4 v4 = *(const float4 *)&v_s[jj + u][4 * (c + 8 * i)];
+                    acc[i].x += pj[u] * v4.x;
+                    acc[i].y += pj[u] * v4.y;
+                    acc[i].z += pj[u] * v4.z;
+                    acc[i].w += pj[u] * v4.w;
+                }
         }
     }
 
@@ -166,7 +181,9 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
         const float inv = 1.f / l_run;
         float *orow = (float *)out.o + prow * D;
 #pragma unroll
-        for (int k = 0; k < D / 8; ++k) orow[c + 8 * k] = acc[k] * inv;
+        for (int i = 0; i < D / 32; ++i)
+            *(float4 *)(orow + 4 * (c + 8 * i)) = make_float4(acc[i].x * inv, acc[i].y * inv, acc[i].z * inv,
+                                                              acc[i].w * inv);
         if (c == 0) out.lse[prow] = (m_run + log2f(l_run)) * kLn2;
     } else if (c == 0) {
         out.lse[prow] = -INFINITY;
