@@ -59,7 +59,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="C3", help="C1..C5 (the headline metric is quoted on C3)")
+    ap.add_argument("--workload", default="C3",
+                    help="C1..C5 (the headline metric is quoted on C3); D1, D2: cross-attention over the cache only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hot", action="store_true", help="also time with one K/V copy (cache-resident)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -106,10 +107,13 @@ def main():
     n_splits = ls.ls_prefix_num_splits(db.desc)
     stream = torch.cuda.current_stream()
 
-    def call(i):
-        r = i % n_rot
-        ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.k_tree, db.v_tree,
-                               db.parents, db.out, db.lse, ws, stream=stream)
+    def call(i, r=None):
+        r = i % n_rot if r is None else r
+        if w.kind == "cross":  # cached keys only: the draft model's cross-attention over the target cache
+            ls.ls_cache_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.out, db.lse, ws, stream=stream)
+        else:
+            ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.k_tree, db.v_tree,
+                                   db.parents, db.out, db.lse, ws, stream=stream)
 
     for i in range(args.warmup):
         call(i)
@@ -162,13 +166,11 @@ def main():
     hot_us = None
     if args.hot:
         for i in range(args.warmup):
-            ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[0], v_rot[0], db.prefix_lens, db.k_tree, db.v_tree,
-                                   db.parents, db.out, db.lse, ws, stream=stream)
+            call(i, 0)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
-            ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[0], v_rot[0], db.prefix_lens, db.k_tree, db.v_tree,
-                                   db.parents, db.out, db.lse, ws, stream=stream)
+            call(i, 0)
         torch.cuda.synchronize()
         hot_us = (time.perf_counter() - t0) / args.steps * 1e6
 
@@ -200,11 +202,12 @@ def main():
         rng = np.random.default_rng(7)
         # a first small sample sizes the run: the whole call if it fits the budget, else a row sample
         t0 = time.perf_counter()
-        oracle_full(batch, rows_per_seq=16, rng=rng)
+        okw = {"use_tree": False} if w.kind == "cross" else {}
+        oracle_full(batch, rows_per_seq=16, rng=rng, **okw)
         per_row = (time.perf_counter() - t0) / (16 * w.batch)
         n_rows = int(min(w.n_q_heads * w.n_tree, max(16, budget / per_row / w.batch)))
         t0 = time.perf_counter()
-        oracle_full(batch, rows_per_seq=n_rows, rng=rng)
+        oracle_full(batch, rows_per_seq=n_rows, rng=rng, **okw)
         dt = time.perf_counter() - t0
         cpu = {"value": dt / (n_rows * w.batch) * rows_total * 1e6, "unit": "us per verify call", "cores": oracle.num_threads(),
                "kind": "oracle",
@@ -213,7 +216,8 @@ def main():
 
     out = {
         "metric": "us per verify call (hybrid tree attention, 32k-token prefix)" if w.name == "C3" else
-                  f"us per verify call (hybrid tree attention, workload {w.name})",
+                  (f"us per cross-attention call over the cache (workload {w.name})" if w.kind == "cross" else
+                   f"us per verify call (hybrid tree attention, workload {w.name})"),
         "value": us_per_call,
         "unit": "us",
         "n_gpus": 1,

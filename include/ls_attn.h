@@ -143,6 +143,21 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q,
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Unmasked attention of the query rows over the cached keys only, merged over the key
+ * splits: out = o_cache, lse = LSE_cache of the appendix.  This is the cross-attention over
+ * the target model's KV cache that the draft model of Section 3.1 runs at every drafting
+ * step (its n_tree is the number of tokens drafted in that step), and the cached half of
+ * ls_hybrid_tree_attn on its own.  desc->kt_stride / vt_stride are checked like the other
+ * strides but address nothing.  Arguments,
+ * workspace size and layout rules as for ls_hybrid_tree_attn; a sequence with prefix
+ * length 0 gets zeros and lse = -inf.
+ */
+int ls_cache_attn(const ls_desc *desc, const void *q,
+                  const void *k_cache, const void *v_cache, const int32_t *prefix_lens,
+                  void *out, float *lse,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * DEVICE address, inside a workspace laid out for `desc`, of the int32[batch] error words
  * that ls_hybrid_tree_attn writes: word b is 1 when sequence b had an invalid parents
  * entry, else 0.  The caller may copy them back after synchronising.  Host-only pointer

@@ -65,12 +65,13 @@ def lib() -> ctypes.CDLL:
     L.ls_workspace_bytes.argtypes = [dp, ctypes.POINTER(_sz)]
     L.ls_workspace_error.argtypes = [dp, _vp, ctypes.POINTER(_vp)]
     L.ls_hybrid_tree_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.ls_cache_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_build_tree_mask.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
     L.ls_prefix_attn_splitkv.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
     L.ls_tree_attn_masked.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
     L.ls_lse_merge.argtypes = [dp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
     for name in ("ls_validate_desc", "ls_validate_parents_host", "ls_prefix_num_splits", "ls_prefix_split_len",
-                 "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_build_tree_mask",
+                 "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_cache_attn", "ls_build_tree_mask",
                  "ls_prefix_attn_splitkv", "ls_tree_attn_masked", "ls_lse_merge"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -187,6 +188,15 @@ def ls_hybrid_tree_attn(desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree, 
                                                         workspace.element_size()), _stream(stream))
     if check:
         _check(st, "ls_hybrid_tree_attn")
+    return int(st)
+
+
+def ls_cache_attn(desc, q, k_cache, v_cache, prefix_lens, out, lse, workspace, stream=None, check: bool = True) -> int:
+    st = lib().ls_cache_attn(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(prefix_lens), _ptr(out),
+                             _ptr(lse), _ptr(workspace), _sz(0 if workspace is None else workspace.numel() *
+                                                             workspace.element_size()), _stream(stream))
+    if check:
+        _check(st, "ls_cache_attn")
     return int(st)
 
 

@@ -339,4 +339,33 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache,
     return LS_OK;
 }
 
+int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                  const int32_t *prefix_lens, void *out, float *lse, void *workspace, size_t workspace_bytes,
+                  void *stream)
+{
+    const int rc = validate(desc);
+    if (rc) return rc;
+    if (!q || !prefix_lens || !out || !lse) return LS_ERR_NULL;
+    if (desc->max_prefix_len > 0 && (!k_cache || !v_cache)) return LS_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return LS_ERR_STRIDE;
+    const SplitPlan plan = plan_splits(*desc, 0);
+    const Workspace w = layout(*desc, plan);
+    if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < w.total) return LS_ERR_WORKSPACE;
+    char *base = (char *)workspace;
+    float *lse_parts = (float *)(base + w.off_lse);
+    void *o_parts = base + w.off_o;
+    hipStream_t s = (hipStream_t)stream;
+    const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, nullptr, nullptr);
+    const bool mfma = prefix_mfma_supports(p, desc->dtype);
+    if (!mfma && desc->dtype == LS_BF16) return LS_ERR_UNSUPPORTED;
+    const Partials parts{o_parts, lse_parts, w.n_parts, 0, desc->dtype == LS_BF16};
+    const hipError_t e = mfma ? launch_prefix_mfma(p, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s)
+                              : launch_prefix_valu(p, desc->dtype, plan, parts, s);
+    if (e != hipSuccess) return LS_ERR_HIP;
+    // the tail kernel without a mask: merge of the split partials only
+    if (launch_tree_merge(p, desc->dtype, nullptr, parts, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)
+        return LS_ERR_HIP;
+    return LS_OK;
+}
+
 }  // extern "C"

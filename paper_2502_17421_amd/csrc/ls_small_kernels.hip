@@ -301,7 +301,7 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
         acc[e] = 0.f;
     }
     float m_run = -INFINITY, l_run = 0.f;
-    for (int w = 0; w < words; ++w) {
+    for (int w = 0; mask != nullptr && w < words; ++w) {  // no mask: no tree part, merge only
         uint64_t bits = mrow[w];
         if (w == words - 1 && (p.n_tree & 63)) bits &= ((uint64_t)1 << (p.n_tree & 63)) - 1;
         while (bits) {

@@ -32,6 +32,7 @@ class Workload:
     max_depth: Optional[int]      # None: unconstrained uniform parents
     max_children: Optional[int]
     seed: int
+    kind: str = "verify"    # "verify": the whole hybrid tree attention; "cross": cached keys only
 
     @property
     def group(self) -> int:
@@ -45,6 +46,10 @@ WORKLOADS = {
     "C3": Workload("C3", "bf16", 1, 32, 8, 128, 64, 32768, 32768, 8, 4, 1003),
     "C4": Workload("C4", "bf16", 1, 32, 32, 128, 32, 16384, 16384, 6, None, 1004),
     "C5": Workload("C5", "bf16", 4, 40, 8, 128, 128, 16384, 65536, 10, 4, 1005),
+    # Draft-side cross-attention over the target model's KV cache (Section 3.1): one drafting
+    # step of beam width 16 resp. 4 (Appendix "Experiments Details") on the 8B-class GQA shape.
+    "D1": Workload("D1", "bf16", 1, 32, 8, 128, 16, 32768, 32768, None, None, 1011, "cross"),
+    "D2": Workload("D2", "bf16", 1, 32, 8, 128, 4, 32768, 32768, None, None, 1012, "cross"),
 }
 
 

@@ -148,6 +148,9 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_hybrid_tree_attn(dp, one, one, one, one, one, one, one, one, one, odd, 1 << 40, None) == ls.LS_ERR_WORKSPACE
     bad = good_desc(); bad.n_tree = 0
     assert L.ls_hybrid_tree_attn(ctypes.byref(bad), one, one, one, one, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_SHAPE
+    assert L.ls_cache_attn(dp, one, one, None, one, one, one, one, 1 << 40, None) == ls.LS_ERR_NULL
+    assert L.ls_cache_attn(dp, one, one, one, one, one, one, one, 16, None) == ls.LS_ERR_WORKSPACE
+    assert L.ls_cache_attn(dp, one, odd, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_STRIDE
     assert L.ls_build_tree_mask(None, 1, 4, one, None, None) == ls.LS_ERR_NULL
     assert L.ls_build_tree_mask(one, 1, 0, one, None, None) == ls.LS_ERR_SHAPE
     assert L.ls_build_tree_mask(one, 1, 129, one, None, None) == ls.LS_ERR_UNSUPPORTED

@@ -337,6 +337,43 @@ def test_bad_parents_on_device_set_the_error_word():
     assert torch.isfinite(db.out.float()).all()
 
 
+# ------------------------------------- cached keys only (draft-side cross-attention) ----
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,t,plens", [
+    ("bf16", 32, 8, 128, 16, [3000]),        # one drafting step of beam width 16, GQA 4:1
+    ("bf16", 32, 8, 128, 4, [2100]),         # beam width 4
+    ("bf16", 8, 8, 64, 16, [1500, 70, 0]),   # MHA, head_dim 64, a sequence with an empty cache
+    ("f32", 4, 1, 64, 16, [1024]),
+])
+def test_cache_only_attention(dtype, hq, hkv, d, t, plens):
+    rng = np.random.default_rng(950 + hq + t)
+    seqs = [synth.make_sequence(rng, dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n_tree=t,
+                                prefix_len=pl, parents=synth.tree_chain(t), variant="peaked") for pl in plens]
+    w = synth.Workload("case", dtype, len(seqs), hq, hkv, d, t, min(plens), max(plens), None, None, 0, "cross")
+    batch = synth.Batch(w, "peaked", seqs)
+    db = DeviceBatch(batch)
+    out, lse = db.run_cache_only()
+    torch.cuda.synchronize()
+    out, lse = out.float().cpu().numpy(), lse.cpu().numpy()
+    for b, sq in enumerate(seqs):
+        if sq.prefix_len == 0:
+            assert np.all(out[b] == 0) and np.all(np.isneginf(lse[b]))
+            continue
+        ro, rl = oracle.attn_all(sq.q, sq.k_cache, sq.v_cache, sq.k_tree, sq.v_tree, sq.parents, use_tree=False)
+        say(gates(out[b], lse[b], ro, rl, dtype, f"cache only {dtype} hq={hq} t={t} P={sq.prefix_len}", stress=True))
+
+
+def test_cache_only_full_size_d1():
+    w = synth.WORKLOADS["D1"]
+    batch = synth.make_batch(w, "iid")
+    db = DeviceBatch(batch)
+    out, lse = db.run_cache_only()
+    torch.cuda.synchronize()
+    sq = batch.seqs[0]
+    ro, rl = oracle.attn_all(sq.q, sq.k_cache, sq.v_cache, sq.k_tree, sq.v_tree, sq.parents, use_tree=False)
+    say(gates(out[0].float().cpu().numpy(), lse[0].cpu().numpy(), ro, rl, "bf16", "D1 full size, all rows"))
+
+
 # ------------------------------------------------ properties that hold at any size ----
 
 def _prefix_then_merge(db, n_splits, part_dtype):

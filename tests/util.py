@@ -58,6 +58,14 @@ class DeviceBatch:
                                  self.max_prefix_len)
         self.workspace = None
 
+    def run_cache_only(self, stream=None):
+        if self.workspace is None:
+            n = ls.ls_workspace_bytes(self.desc)
+            self.workspace = torch.empty(n, dtype=torch.uint8, device=self.q.device)
+        ls.ls_cache_attn(self.desc, self.q, self.k_cache, self.v_cache, self.prefix_lens, self.out, self.lse,
+                         self.workspace, stream=stream)
+        return self.out, self.lse
+
     def run_full(self, stream=None):
         if self.workspace is None:
             n = ls.ls_workspace_bytes(self.desc)
