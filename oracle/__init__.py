@@ -52,6 +52,10 @@ def _load():
     lib.ls_oracle_attn_rows.restype = ctypes.c_int
     lib.ls_oracle_lse_merge.argtypes = [i64, i32, i32, vp, vp, vp, vp]
     lib.ls_oracle_lse_merge.restype = ctypes.c_int
+    lib.ls_oracle_tree_accept_greedy.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.ls_oracle_tree_accept_greedy.restype = i32
+    lib.ls_oracle_kv_commit.argtypes = [i32, i32, i32, i64, i64, vp, i32, vp, vp]
+    lib.ls_oracle_kv_commit.restype = i64
     _lib = lib
     return lib
 
@@ -133,3 +137,32 @@ def lse_merge(o_parts, lse_parts):
     if rc != 0:
         raise ValueError(f"ls_oracle_lse_merge failed with {rc}")
     return out, lse
+
+
+def tree_accept_greedy(parents, draft_tokens, target_tokens):
+    """One sequence: returns (path [T] int32 root first, padded with -1; length; next_token)."""
+    parents = np.ascontiguousarray(parents, dtype=np.int32)
+    draft = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    target = np.ascontiguousarray(target_tokens, dtype=np.int32)
+    t = parents.shape[0]
+    assert draft.shape == (t,) and target.shape == (t,)
+    path = np.empty(t, dtype=np.int32)
+    nxt = np.zeros(1, dtype=np.int32)
+    n = _load().ls_oracle_tree_accept_greedy(_ptr(parents), _ptr(draft), _ptr(target), t, _ptr(path), _ptr(nxt))
+    if n < 0:
+        raise ValueError("ls_oracle_tree_accept_greedy: bad arguments")
+    return path, int(n), int(nxt[0])
+
+
+def kv_commit(cache, tree, prefix_len, path, path_len):
+    """cache [Hkv,capacity,D], tree [Hkv,T,D] float32: returns (new cache, new prefix length)."""
+    cache = np.array(cache, dtype=np.float32, order="C", copy=True)
+    tree = _f32(tree)
+    path = np.ascontiguousarray(path, dtype=np.int32)
+    hkv, cap, d = cache.shape
+    assert tree.shape[0] == hkv and tree.shape[2] == d
+    n = _load().ls_oracle_kv_commit(hkv, d, tree.shape[1], cap, int(prefix_len), _ptr(path), int(path_len),
+                                    _ptr(tree), _ptr(cache))
+    if n < 0:
+        raise ValueError("ls_oracle_kv_commit: row outside the cache or bad path")
+    return cache, int(n)

@@ -47,6 +47,13 @@
  * than one root is allowed; natural-log LSE of the scaled logits; query head h
  * uses KV head h / (Hq / Hkv); an empty visible set gives lse = -inf, out = 0.
  *
+ * Two integer steps that follow the attention in a verification round are
+ * defined at the end of the file, each with its own comment: the greedy
+ * acceptance walk over the tree and the move of the accepted tokens' K/V rows
+ * into the cache (pins: tests/test_oracle_accept_pins.py -- a hand-worked
+ * case, equality with plain greedy decoding of a toy deterministic model,
+ * an all-paths brute force, and indexing written with numpy).
+ *
  * Pins: tests/test_oracle_pins.py (brute force, hand-computed case, closed
  * forms, split/merge invariant, chain == causal and other textbook special
  * cases against torch's CPU scaled_dot_product_attention).
@@ -278,4 +285,85 @@ int ls_oracle_lse_merge(int64_t n_rows, int32_t n_parts, int32_t head_dim,
         lse[r] = acc_lse;
     }
     return 0;
+}
+
+/*
+ * Greedy (temperature 0) acceptance of a speculation tree -- the verification
+ * step that follows the target model's pass over the tree (Section 2.1 "Fast
+ * Tree Attention": the target verifies all candidate sequences at once without
+ * altering the final result; Section 4.1 evaluates at T = 0).
+ *
+ * The paper does not print the rule; the reading taken is the one that makes
+ * the output identical to plain greedy decoding.  Node 0 holds the last token
+ * already sampled and is always on the path.  draft_tokens[i] is the token at
+ * node i, target_tokens[i] the target model's most likely next token after
+ * the sequence that ends at node i.  Walk down from node 0: at node cur, the
+ * child whose token equals target_tokens[cur] continues the path (the lowest
+ * node index if several siblings carry that token); if there is none the walk
+ * stops.  next_token is target_tokens at the last node of the path, the token
+ * the target contributes itself.
+ *
+ *   path     [n_tree] out: node indices root first, the rest filled with -1
+ *   returns the number of nodes on the path (>= 1), or -1 on bad arguments.
+ */
+int32_t ls_oracle_tree_accept_greedy(const int32_t *parents, const int32_t *draft_tokens,
+                                     const int32_t *target_tokens, int32_t n_tree,
+                                     int32_t *path, int32_t *next_token)
+{
+    if (!parents || !draft_tokens || !target_tokens || !path || !next_token || n_tree <= 0)
+        return -1;
+    if (ls_oracle_check_parents(parents, n_tree) != 0)
+        return -1;
+    for (int32_t i = 0; i < n_tree; ++i)
+        path[i] = -1;
+    int32_t cur = 0, len = 1;
+    path[0] = 0;
+    for (;;) {
+        int32_t next = -1;
+        for (int32_t j = cur + 1; j < n_tree; ++j) {
+            if (parents[j] == cur && draft_tokens[j] == target_tokens[cur]) {
+                next = j;
+                break;
+            }
+        }
+        if (next < 0)
+            break;
+        path[len++] = next;
+        cur = next;
+    }
+    *next_token = target_tokens[cur];
+    return len;
+}
+
+/*
+ * Moving the accepted tokens' keys and values into the cache (the "KV cache
+ * movement" after verification of the appendix "Experiments Details"; the
+ * target model updates its cache only once verification is complete, Section
+ * 3.2 "Flash Noisy Training").  For one sequence and one tensor (K or V):
+ *
+ *   cache [n_kv_heads][capacity][head_dim], tree [n_kv_heads][n_tree][head_dim]
+ *   cache[g][prefix_len + j][:] = tree[g][path[j]][:]   for j < path_len.
+ *
+ * Values are copied bit for bit (float holds bf16 and fp32 exactly).  Returns
+ * the new prefix length, or -1 if a row would fall outside the cache or a
+ * path entry is not a node.
+ */
+int64_t ls_oracle_kv_commit(int32_t n_kv_heads, int32_t head_dim, int32_t n_tree, int64_t capacity,
+                            int64_t prefix_len, const int32_t *path, int32_t path_len,
+                            const float *tree, float *cache)
+{
+    if (!path || !tree || !cache || n_kv_heads <= 0 || head_dim <= 0 || n_tree <= 0)
+        return -1;
+    if (path_len < 0 || prefix_len < 0 || prefix_len + path_len > capacity)
+        return -1;
+    for (int32_t j = 0; j < path_len; ++j)
+        if (path[j] < 0 || path[j] >= n_tree)
+            return -1;
+    for (int32_t g = 0; g < n_kv_heads; ++g)
+        for (int32_t j = 0; j < path_len; ++j) {
+            const float *src = tree + ((size_t)g * n_tree + path[j]) * head_dim;
+            float *dst = cache + ((size_t)g * capacity + prefix_len + j) * head_dim;
+            memcpy(dst, src, (size_t)head_dim * sizeof(float));
+        }
+    return prefix_len + path_len;
 }
