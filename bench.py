@@ -54,13 +54,86 @@ def flops_prefix(w, prefix_lens):
     return sum(4 * w.n_q_heads * w.n_tree * int(p) * w.head_dim for p in prefix_lens)
 
 
+def bench_accept_commit(args, w):
+    """Workloads of kind "accept": greedy tree acceptance followed by the KV commit of the accepted
+    path, timed as one step.  Both kernels are latency-bound (a tree has at most 128 nodes)."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2502_17421_amd import binding as ls
+    from paper_2502_17421_amd import synth
+
+    rng = np.random.default_rng(w.seed)
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    e = 2 if w.dtype == "bf16" else 4
+    cap = w.prefix_hi + w.n_tree
+    parents, draft, target, plens = [], [], [], []
+    for b in range(w.batch):
+        par = synth.tree_constrained(rng, w.n_tree, w.max_depth, w.max_children)
+        d, g = synth.make_tokens(rng, par, 32000, 0.7)
+        parents.append(par), draft.append(d), target.append(g)
+        plens.append(int(rng.integers(w.prefix_lo, w.prefix_hi + 1)))
+    parents, draft, target = np.stack(parents), np.stack(draft), np.stack(target)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    kc = torch.zeros((w.batch, w.n_kv_heads, cap, w.head_dim), dtype=dt, device="cuda")
+    vc = torch.zeros_like(kc)
+    kt = torch.randn((w.batch, w.n_kv_heads, w.n_tree, w.head_dim), device="cuda").to(dt)
+    vt = torch.randn((w.batch, w.n_kv_heads, w.n_tree, w.head_dim), device="cuda").to(dt)
+    q = torch.zeros((w.batch, w.n_q_heads, w.n_tree, w.head_dim), dtype=dt, device="cuda")
+    desc = ls.make_desc(q, kc, vc, kt, vt, q, cap)
+    d_par, d_draft, d_target, d_plens = dev(parents), dev(draft), dev(target), dev(plens)
+    path = torch.empty((w.batch, w.n_tree), dtype=torch.int32, device="cuda")
+    n = torch.empty((w.batch,), dtype=torch.int32, device="cuda")
+    nxt, new_lens, err = torch.empty_like(n), torch.empty_like(n), torch.empty_like(n)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        ls.ls_tree_accept_greedy(d_par, d_draft, d_target, path, n, nxt, err, stream=stream)
+        ls.ls_kv_commit(desc, kt, vt, path, n, d_plens, kc, vc, new_lens, err, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) * 1e6 / args.steps
+    lens = n.cpu().numpy()
+    moved = int(lens.sum()) * 2 * w.n_kv_heads * w.head_dim * e * 2   # K and V rows, read + written
+    cpu = None
+    if not args.no_cpu_baseline:
+        reps = 2000
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            for b in range(w.batch):
+                oracle.tree_accept_greedy(parents[b], draft[b], target[b])
+        cpu = {"value": (time.perf_counter() - t0) * 1e6 / reps, "unit": "us per acceptance of the batch", "cores": 1,
+               "kind": "oracle", "sample": f"{reps} repetitions of the acceptance walk over the same {w.batch} tree(s)"}
+        for b in range(w.batch):
+            rp, rn, _ = oracle.tree_accept_greedy(parents[b], draft[b], target[b])
+            assert rn == lens[b] and rp.tolist() == path[b].cpu().tolist()
+    print(json.dumps({
+        "metric": f"us per acceptance + KV commit (workload {w.name})", "value": us, "unit": "us", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": us * 1e-3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int32 / " + w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_kv_heads} kv heads, head_dim {w.head_dim}, n_tree "
+                               f"{w.n_tree}, accepted path lengths {lens.tolist()}"},
+        "roofline": {"bound": "hbm", "achieved": moved / us * 1e-3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": moved / us * 1e-3 / HBM_PEAK_GBS, "traffic": None,
+                     "note": "two launches of a few microseconds each: launch latency, not bandwidth, sets the time"},
+        "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="C3",
-                    help="C1..C5 (the headline metric is quoted on C3); D1, D2: cross-attention over the cache only")
+                    help="C1..C5 (the headline metric is quoted on C3); D1, D2: cross-attention over the cache only; "
+                         "A3, A5: greedy acceptance + KV commit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hot", action="store_true", help="also time with one K/V copy (cache-resident)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -94,6 +167,8 @@ def main():
         return
 
     w = synth.WORKLOADS[args.workload]
+    if w.kind == "accept":
+        return bench_accept_commit(args, w)
     batch = synth.make_batch(w, "iid")
     db = DeviceBatch(batch)
     plens = batch.prefix_lens.tolist()

@@ -222,6 +222,53 @@ int ls_lse_merge(const ls_desc *desc, int32_t n_parts, int32_t part_dtype,
                  const void *o_parts, const float *lse_parts,
                  void *out, float *lse, void *stream);
 
+/* ---- after the attention: the rest of a verification round -------------------------- */
+
+/*
+ * Greedy (temperature 0) acceptance of the speculation tree, once the target model has run
+ * over it (Section 2.1 "Fast Tree Attention": all candidate sequences are verified in one
+ * pass without altering the final result; Section 4.1 evaluates at T = 0).  Node 0 holds
+ * the last token already sampled and is always accepted.  From node cur the path continues
+ * with the child whose token equals target_tokens[cur] (the lowest node index if several
+ * siblings carry it) and ends where no child does; the output is then identical to plain
+ * greedy decoding of the target model.
+ *   parents        DEVICE int32[batch, n_tree], as for ls_build_tree_mask (an invalid entry
+ *                  makes the node a root and sets err_flag)
+ *   draft_tokens   DEVICE int32[batch, n_tree]  token at each node
+ *   target_tokens  DEVICE int32[batch, n_tree]  the target model's most likely next token
+ *                  after the sequence that ends at the node
+ *   accept_path    DEVICE int32[batch, n_tree]  out: node indices root first, then -1
+ *   accept_len     DEVICE int32[batch]          out: nodes on the path, >= 1
+ *   next_token     DEVICE int32[batch]          out: target_tokens at the last accepted node
+ *   err_flag       DEVICE int32[batch] or NULL  out: 1 if a parents entry was invalid, else 0
+ * n_tree <= LS_MAX_TREE, batch <= 65535.
+ */
+int ls_tree_accept_greedy(const int32_t *parents, const int32_t *draft_tokens,
+                          const int32_t *target_tokens, int32_t batch, int32_t n_tree,
+                          int32_t *accept_path, int32_t *accept_len, int32_t *next_token,
+                          int32_t *err_flag, void *stream);
+
+/*
+ * Moves the accepted tokens' key and value rows from the tree buffers into the cache (the
+ * target's cache is updated only when verification is complete, Section 3.2; the "KV cache
+ * movement" of the appendix "Experiments Details"):
+ *   cache[b, g, prefix_lens[b] + j, :] = tree[b, g, accept_path[b, j], :],  j < accept_len[b]
+ * for K and V, bit for bit.  desc gives dtype, shapes and the strides of all four buffers
+ * (q_stride / o_stride are checked but address nothing); desc->max_prefix_len is the number
+ * of rows the cache holds per sequence.  Rows that would fall outside it, and everything
+ * from the first path entry that is not a node, are not written.
+ *   k_tree, v_tree    DEVICE, read      k_cache, v_cache  DEVICE, rows written in place
+ *   accept_path, accept_len, prefix_lens  DEVICE int32, as above (read only)
+ *   new_prefix_lens   DEVICE int32[batch] or NULL, out: prefix_lens[b] + rows moved; must
+ *                     not alias prefix_lens (other workgroups still read it)
+ *   err_flag          DEVICE int32[batch] or NULL, out: 1 if fewer than accept_len[b] rows
+ *                     were moved, else 0
+ */
+int ls_kv_commit(const ls_desc *desc, const void *k_tree, const void *v_tree,
+                 const int32_t *accept_path, const int32_t *accept_len, const int32_t *prefix_lens,
+                 void *k_cache, void *v_cache, int32_t *new_prefix_lens, int32_t *err_flag,
+                 void *stream);
+
 #ifdef __cplusplus
 }
 #endif

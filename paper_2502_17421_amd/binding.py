@@ -70,9 +70,12 @@ def lib() -> ctypes.CDLL:
     L.ls_prefix_attn_splitkv.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
     L.ls_tree_attn_masked.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
     L.ls_lse_merge.argtypes = [dp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+    L.ls_tree_accept_greedy.argtypes = [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+    L.ls_kv_commit.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
     for name in ("ls_validate_desc", "ls_validate_parents_host", "ls_prefix_num_splits", "ls_prefix_split_len",
                  "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_cache_attn", "ls_build_tree_mask",
-                 "ls_prefix_attn_splitkv", "ls_tree_attn_masked", "ls_lse_merge"):
+                 "ls_prefix_attn_splitkv", "ls_tree_attn_masked", "ls_lse_merge", "ls_tree_accept_greedy",
+                 "ls_kv_commit"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -233,4 +236,26 @@ def ls_lse_merge(desc, n_parts, o_parts, lse_parts, out, lse, stream=None, check
                             _ptr(out), _ptr(lse), _stream(stream))
     if check:
         _check(st, "ls_lse_merge")
+    return int(st)
+
+
+def ls_tree_accept_greedy(parents, draft_tokens, target_tokens, accept_path, accept_len, next_token, err_flag=None,
+                          stream=None, check: bool = True) -> int:
+    """All tensors device int32: parents/draft_tokens/target_tokens/accept_path [batch, n_tree];
+    accept_len/next_token/err_flag [batch]."""
+    st = lib().ls_tree_accept_greedy(_ptr(parents), _ptr(draft_tokens), _ptr(target_tokens), parents.shape[0],
+                                     parents.shape[1], _ptr(accept_path), _ptr(accept_len), _ptr(next_token),
+                                     _ptr(err_flag), _stream(stream))
+    if check:
+        _check(st, "ls_tree_accept_greedy")
+    return int(st)
+
+
+def ls_kv_commit(desc, k_tree, v_tree, accept_path, accept_len, prefix_lens, k_cache, v_cache, new_prefix_lens=None,
+                 err_flag=None, stream=None, check: bool = True) -> int:
+    st = lib().ls_kv_commit(ctypes.byref(desc), _ptr(k_tree), _ptr(v_tree), _ptr(accept_path), _ptr(accept_len),
+                            _ptr(prefix_lens), _ptr(k_cache), _ptr(v_cache), _ptr(new_prefix_lens), _ptr(err_flag),
+                            _stream(stream))
+    if check:
+        _check(st, "ls_kv_commit")
     return int(st)

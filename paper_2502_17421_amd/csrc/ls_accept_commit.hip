@@ -1,0 +1,173 @@
+// The two integer steps that follow the attention in a verification round: greedy acceptance
+// of the speculation tree (Section 2.1 "Fast Tree Attention", evaluated at T = 0 in Section
+// 4.1) and the move of the accepted tokens' key/value rows into the cache (the cache is
+// updated only once verification is complete, Section 3.2; "KV cache movement" in the
+// appendix "Experiments Details").  Both are latency-bound: a tree has at most 128 nodes.
+#include "ls_internal.hpp"
+
+namespace ls {
+
+namespace {
+
+// One workgroup per sequence, one thread per node.
+//   match[i]   node i carries the token the target predicts after its parent
+//   chosen[i]  match[i] and no earlier sibling matches (lowest index wins among equal tokens)
+//   node i is on the accepted path iff every node from i up to, not including, node 0 is
+//   chosen and that walk ends at node 0.  At most one child of a node is chosen, so the
+//   accepted nodes form one root path and a node's position on it is its depth.
+__global__ void __launch_bounds__(LS_MAX_TREE)
+tree_accept_kernel(const int32_t *__restrict__ parents, const int32_t *__restrict__ draft,
+                   const int32_t *__restrict__ target, int32_t n_tree, int32_t *__restrict__ path,
+                   int32_t *__restrict__ accept_len, int32_t *__restrict__ next_token,
+                   int32_t *__restrict__ err_flag)
+{
+    __shared__ int32_t par[LS_MAX_TREE];
+    __shared__ int32_t tgt[LS_MAX_TREE];
+    __shared__ uint8_t match[LS_MAX_TREE];
+    __shared__ uint8_t chosen[LS_MAX_TREE];
+    __shared__ int32_t len_sh;
+    const int b = blockIdx.x;
+    const int i = threadIdx.x;
+    const bool live = i < n_tree;
+    parents += (size_t)b * n_tree;
+    draft += (size_t)b * n_tree;
+    target += (size_t)b * n_tree;
+    path += (size_t)b * n_tree;
+
+    int bad = 0;
+    int32_t my_token = 0;
+    if (live) {
+        int32_t p = parents[i];
+        if (p < -1 || p >= i) {  // not a forest in topological order: treat the node as a root
+            bad = 1;
+            p = -1;
+        }
+        par[i] = p;
+        tgt[i] = target[i];
+        my_token = draft[i];
+        path[i] = -1;
+    }
+    if (i == 0) len_sh = 0;
+    __syncthreads();
+    if (live) match[i] = i > 0 && par[i] >= 0 && my_token == tgt[par[i]];
+    __syncthreads();
+    if (live) {
+        bool first = match[i];
+        for (int j = 1; j < i && first; ++j)
+            if (par[j] == par[i] && match[j]) first = false;
+        chosen[i] = first;
+    }
+    __syncthreads();
+    if (live) {
+        int cur = i, depth = 0;
+        bool on_path = true;
+        while (cur > 0) {  // par[cur] < cur, so this ends after at most i steps
+            if (!chosen[cur]) {
+                on_path = false;
+                break;
+            }
+            cur = par[cur];
+            ++depth;
+        }
+        on_path = on_path && cur == 0;  // a walk that ends at another root is off the path
+        if (on_path) {
+            path[depth] = i;
+            atomicMax(&len_sh, depth + 1);
+        }
+    }
+    __syncthreads();
+    if (live) {
+        // the deepest accepted node reports the token the target adds itself
+        int cur = i, depth = 0;
+        bool on_path = true;
+        while (cur > 0) {
+            if (!chosen[cur]) {
+                on_path = false;
+                break;
+            }
+            cur = par[cur];
+            ++depth;
+        }
+        if (on_path && cur == 0 && depth + 1 == len_sh) {
+            next_token[b] = tgt[i];
+            accept_len[b] = len_sh;
+        }
+    }
+    const int any_bad = __syncthreads_or(bad);
+    if (i == 0 && err_flag) err_flag[b] = any_bad ? 1 : 0;
+}
+
+// One workgroup per (sequence, KV head): 16-byte pieces of the accepted rows of K and V are
+// copied from the tree buffers to cache rows prefix_len, prefix_len + 1, ...  The number of
+// rows moved is the longest prefix of the path whose entries are nodes and whose target rows
+// exist; anything shorter than accept_len is reported in err_flag.
+__global__ void __launch_bounds__(256)
+kv_commit_kernel(Problem p, int elem_bytes, const int32_t *__restrict__ accept_path,
+                 const int32_t *__restrict__ accept_len, uint8_t *__restrict__ k_cache,
+                 uint8_t *__restrict__ v_cache, int32_t *__restrict__ new_prefix_lens,
+                 int32_t *__restrict__ err_flag)
+{
+    __shared__ int32_t path[LS_MAX_TREE];
+    __shared__ int32_t n_sh;
+    const int b = blockIdx.x / p.n_kv_heads;
+    const int g = blockIdx.x % p.n_kv_heads;
+    const int tid = threadIdx.x;
+
+    int plen = p.prefix_lens[b];
+    plen = plen < 0 ? 0 : (plen > p.max_prefix_len ? p.max_prefix_len : plen);
+    int want = accept_len[b];
+    want = want < 0 ? 0 : (want > p.n_tree ? p.n_tree : want);
+    int room = p.max_prefix_len - plen;
+    int n = want < room ? want : room;
+    if (tid == 0) n_sh = n;
+    __syncthreads();
+    if (tid < n) {
+        const int32_t node = accept_path[(size_t)b * p.n_tree + tid];
+        path[tid] = node;
+        if (node < 0 || node >= p.n_tree) atomicMin(&n_sh, tid);  // stop before the first bad entry
+    }
+    __syncthreads();
+    n = n_sh;
+
+    const int chunks = p.head_dim * elem_bytes / 16;  // 16-byte pieces per row
+    const uint8_t *kt = (const uint8_t *)p.k_tree + (b * p.kt_stride[0] + g * p.kt_stride[1]) * elem_bytes;
+    const uint8_t *vt = (const uint8_t *)p.v_tree + (b * p.vt_stride[0] + g * p.vt_stride[1]) * elem_bytes;
+    uint8_t *kc = k_cache + (b * p.kc_stride[0] + g * p.kc_stride[1]) * elem_bytes;
+    uint8_t *vc = v_cache + (b * p.vc_stride[0] + g * p.vc_stride[1]) * elem_bytes;
+    for (int e = tid; e < n * chunks; e += blockDim.x) {
+        const int j = e / chunks, c = e % chunks;
+        const int64_t node = path[j];
+        const int64_t row = plen + j;
+        const uint4 kv = *(const uint4 *)(kt + node * p.kt_stride[2] * elem_bytes + c * 16);
+        const uint4 vv = *(const uint4 *)(vt + node * p.vt_stride[2] * elem_bytes + c * 16);
+        *(uint4 *)(kc + row * p.kc_stride[2] * elem_bytes + c * 16) = kv;
+        *(uint4 *)(vc + row * p.vc_stride[2] * elem_bytes + c * 16) = vv;
+    }
+    if (g == 0 && tid == 0) {
+        if (new_prefix_lens) new_prefix_lens[b] = plen + n;
+        if (err_flag) err_flag[b] = n < accept_len[b] ? 1 : 0;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_tree_accept(const int32_t *parents, const int32_t *draft_tokens, const int32_t *target_tokens,
+                              int32_t batch, int32_t n_tree, int32_t *accept_path, int32_t *accept_len,
+                              int32_t *next_token, int32_t *err_flag, hipStream_t stream)
+{
+    hipLaunchKernelGGL(tree_accept_kernel, dim3(batch), dim3(LS_MAX_TREE), 0, stream, parents, draft_tokens,
+                       target_tokens, n_tree, accept_path, accept_len, next_token, err_flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_commit(const Problem &p, int dtype, const int32_t *accept_path, const int32_t *accept_len,
+                            void *k_cache, void *v_cache, int32_t *new_prefix_lens, int32_t *err_flag,
+                            hipStream_t stream)
+{
+    const int elem_bytes = dtype == LS_BF16 ? 2 : 4;
+    hipLaunchKernelGGL(kv_commit_kernel, dim3(p.batch * p.n_kv_heads), dim3(256), 0, stream, p, elem_bytes,
+                       accept_path, accept_len, (uint8_t *)k_cache, (uint8_t *)v_cache, new_prefix_lens, err_flag);
+    return hipGetLastError();
+}
+
+}  // namespace ls

@@ -368,4 +368,34 @@ int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const
     return LS_OK;
 }
 
+int ls_tree_accept_greedy(const int32_t *parents, const int32_t *draft_tokens, const int32_t *target_tokens,
+                          int32_t batch, int32_t n_tree, int32_t *accept_path, int32_t *accept_len,
+                          int32_t *next_token, int32_t *err_flag, void *stream)
+{
+    if (!parents || !draft_tokens || !target_tokens || !accept_path || !accept_len || !next_token) return LS_ERR_NULL;
+    if (batch <= 0 || n_tree <= 0) return LS_ERR_SHAPE;
+    if (n_tree > LS_MAX_TREE || batch > 65535) return LS_ERR_UNSUPPORTED;
+    return launch_tree_accept(parents, draft_tokens, target_tokens, batch, n_tree, accept_path, accept_len, next_token,
+                              err_flag, (hipStream_t)stream) == hipSuccess
+               ? LS_OK
+               : LS_ERR_HIP;
+}
+
+int ls_kv_commit(const ls_desc *desc, const void *k_tree, const void *v_tree, const int32_t *accept_path,
+                 const int32_t *accept_len, const int32_t *prefix_lens, void *k_cache, void *v_cache,
+                 int32_t *new_prefix_lens, int32_t *err_flag, void *stream)
+{
+    const int rc = validate(desc);
+    if (rc) return rc;
+    if (!k_tree || !v_tree || !accept_path || !accept_len || !prefix_lens || !k_cache || !v_cache) return LS_ERR_NULL;
+    if (new_prefix_lens == prefix_lens) return LS_ERR_NULL;
+    if (!aligned16(k_tree) || !aligned16(v_tree) || !aligned16(k_cache) || !aligned16(v_cache)) return LS_ERR_STRIDE;
+    if ((int64_t)desc->batch * desc->n_kv_heads > 0x7fffffff) return LS_ERR_UNSUPPORTED;
+    const Problem p = make_problem(*desc, nullptr, k_cache, v_cache, prefix_lens, k_tree, v_tree);
+    return launch_kv_commit(p, desc->dtype, accept_path, accept_len, k_cache, v_cache, new_prefix_lens, err_flag,
+                            (hipStream_t)stream) == hipSuccess
+               ? LS_OK
+               : LS_ERR_HIP;
+}
+
 }  // extern "C"

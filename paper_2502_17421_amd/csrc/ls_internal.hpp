@@ -131,4 +131,11 @@ hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, 
                              int32_t n_cache_parts, void *out, const int64_t o_stride[3], float *lse,
                              hipStream_t stream);
 
+hipError_t launch_tree_accept(const int32_t *parents, const int32_t *draft_tokens, const int32_t *target_tokens,
+                              int32_t batch, int32_t n_tree, int32_t *accept_path, int32_t *accept_len,
+                              int32_t *next_token, int32_t *err_flag, hipStream_t stream);
+hipError_t launch_kv_commit(const Problem &p, int dtype, const int32_t *accept_path, const int32_t *accept_len,
+                            void *k_cache, void *v_cache, int32_t *new_prefix_lens, int32_t *err_flag,
+                            hipStream_t stream);
+
 }  // namespace ls

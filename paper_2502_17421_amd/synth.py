@@ -32,7 +32,7 @@ class Workload:
     max_depth: Optional[int]      # None: unconstrained uniform parents
     max_children: Optional[int]
     seed: int
-    kind: str = "verify"    # "verify": the whole hybrid tree attention; "cross": cached keys only
+    kind: str = "verify"    # "verify": hybrid tree attention; "cross": cached keys only; "accept": acceptance + KV commit
 
     @property
     def group(self) -> int:
@@ -50,6 +50,10 @@ WORKLOADS = {
     # step of beam width 16 resp. 4 (Appendix "Experiments Details") on the 8B-class GQA shape.
     "D1": Workload("D1", "bf16", 1, 32, 8, 128, 16, 32768, 32768, None, None, 1011, "cross"),
     "D2": Workload("D2", "bf16", 1, 32, 8, 128, 4, 32768, 32768, None, None, 1012, "cross"),
+    # The steps after the attention in a verification round (greedy acceptance + KV commit) on
+    # the C3 and C5 shapes; "kind" accept.
+    "A3": Workload("A3", "bf16", 1, 32, 8, 128, 64, 32768, 32768, 8, 4, 1023, "accept"),
+    "A5": Workload("A5", "bf16", 4, 40, 8, 128, 128, 16384, 65536, 10, 4, 1025, "accept"),
 }
 
 
@@ -223,3 +227,17 @@ def make_batch(w: Workload, variant: str = "iid", *, prefix_override: Optional[i
                                         n_tree=n_tree, prefix_len=plen, parents=parents,
                                         variant=variant))
     return batch
+
+
+def make_tokens(rng: np.random.Generator, parents: np.ndarray, vocab: int = 32000, p_follow: float = 0.6):
+    """Token ids for a verification round over a tree: (draft_tokens [T], target_tokens [T]).
+    target_tokens[i] stands for the target model's prediction after node i and is drawn
+    uniformly; a non-root node repeats its parent's prediction with probability p_follow
+    (so accepted paths of several nodes occur) and is drawn uniformly otherwise."""
+    t = len(parents)
+    target = rng.integers(0, vocab, size=t).astype(np.int32)
+    draft = rng.integers(0, vocab, size=t).astype(np.int32)
+    for i in range(1, t):
+        if parents[i] >= 0 and rng.random() < p_follow:
+            draft[i] = target[parents[i]]
+    return draft, target

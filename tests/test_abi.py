@@ -161,6 +161,12 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_lse_merge(dp, 0, ls.LS_F32, one, one, one, one, None) == ls.LS_ERR_SHAPE
     assert L.ls_lse_merge(dp, 2, ls.LS_F32, one, one, None, one, None) == ls.LS_ERR_NULL
     assert L.ls_lse_merge(dp, 2, 9, one, one, one, one, None) == ls.LS_ERR_DTYPE
+    assert L.ls_tree_accept_greedy(one, one, None, 1, 4, one, one, one, None, None) == ls.LS_ERR_NULL
+    assert L.ls_tree_accept_greedy(one, one, one, 0, 4, one, one, one, None, None) == ls.LS_ERR_SHAPE
+    assert L.ls_tree_accept_greedy(one, one, one, 1, 129, one, one, one, None, None) == ls.LS_ERR_UNSUPPORTED
+    assert L.ls_kv_commit(dp, one, one, one, one, one, None, one, None, None, None) == ls.LS_ERR_NULL
+    assert L.ls_kv_commit(dp, one, one, one, one, one, one, one, one, None, None) == ls.LS_ERR_NULL   # aliasing lengths
+    assert L.ls_kv_commit(dp, one, odd, one, one, one, one, one, None, None, None) == ls.LS_ERR_STRIDE
 
 
 def test_binding_raises_when_library_is_missing(tmp_path, monkeypatch):
