@@ -247,9 +247,19 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     static_assert(PD >= 1 && PD <= 2, "prefetch distance");
     const int n_tiles = (k_hi - k_lo + TK - 1) / TK;
     const int n_prologue = n_tiles < PD ? n_tiles : PD;
+    // Tile order: the softmax does not care in which order keys arrive, so split s starts at
+    // its tile (s mod n_tiles) and wraps around.  All workgroups start together; with every
+    // split reading from its first row their addresses would differ by multiples of the split
+    // size only and crowd a few memory channels.
+    const int rot = split % n_tiles;
+    auto tile_k0 = [&](int t) {
+        int tt = t + rot;
+        tt = tt >= n_tiles ? tt - n_tiles : tt;
+        return k_lo + tt * TK;
+    };
 #pragma unroll
     for (int s = 0; s < PD; ++s)
-        if (s < n_prologue) issue_tile(k_lo + s * TK, s);
+        if (s < n_prologue) issue_tile(tile_k0(s), s);
 
     // collect Q: everything older than the prologue tiles has landed
     if (PD >= 2 && n_prologue == 2) wait_vmem<(PD >= 2 ? 2 : 1) * INFLIGHT>();
@@ -387,10 +397,10 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
 
     wait_tile(0);
     __syncthreads();
-    if (PD < n_tiles) issue_tile(k_lo + PD * TK, PD % NS);
+    if (PD < n_tiles) issue_tile(tile_k0(PD), PD % NS);
     fetch_k(smem, 0, k_frag);
     s_cur = score(k_frag);
-    mask_tail(s_cur, k_lo);
+    mask_tail(s_cur, tile_k0(0));
     raise_reference(s_cur);  // sets m_run from the first 32 keys (at least one of them is valid)
 
     // one block: consumes s_cur / p_prev / v_frag, leaves the next step's in their place
@@ -420,30 +430,37 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     for (int t = 0; t + 1 < n_tiles; ++t) {
         const uint8_t *ks = smem + (t % NS) * STAGEB;
         const uint8_t *vs = ks + TILEB;
-        const int k0 = k_lo + t * TK;
+        const int k0 = tile_k0(t);
         // first half of tile t: the next step is the second half of the same tile
         block(yes{}, ks, 1, vs, 0, k0 + SUB);
         // second half: the next step opens tile t+1, which needs the barrier
         wait_tile(t + 1);
         __syncthreads();  // tile t+1 is complete in LDS; nobody reads tile t-1 any more
-        if (t + 1 + PD < n_tiles) issue_tile(k_lo + (t + 1 + PD) * TK, (t + 1 + PD) % NS);
-        block(yes{}, smem + ((t + 1) % NS) * STAGEB, 0, vs, 1, k0 + TK);
+        if (t + 1 + PD < n_tiles) issue_tile(tile_k0(t + 1 + PD), (t + 1 + PD) % NS);
+        block(yes{}, smem + ((t + 1) % NS) * STAGEB, 0, vs, 1, tile_k0(t + 1));
     }
     {  // the last tile: its second half has no successor
         const int t = n_tiles - 1;
         const uint8_t *ks = smem + (t % NS) * STAGEB;
         const uint8_t *vs = ks + TILEB;
-        block(yes{}, ks, 1, vs, 0, k_lo + t * TK + SUB);
+        block(yes{}, ks, 1, vs, 0, tile_k0(t) + SUB);
         block(no{}, ks, 0, vs, 1, 0);
     }
     second_product(v_frag, p_prev);  // the output product of the last step
 
     // ---- epilogue: normalise and store this split's partial result -----------------------
     const float l_tot = half_sum(l_run);
-    if (!q_ok) return;
     const float inv = 1.f / l_tot;
     if (out.o_is_bf16) {
-        uint16_t *orow = (uint16_t *)out.o + part_row * D;
+        // A lane holds 4-element runs of one query row, 256 bytes apart from its neighbours':
+        // stored as they are, every store instruction would touch 32 rows with 16 bytes each.
+        // The rows go through LDS instead and leave as whole rows, 16 bytes per lane.  The
+        // two ring stages after the last tile's are free: no tile was requested into them any
+        // more, and every wave has passed the barrier after which their old tiles were dead.
+        // Each wave owns a quarter of a stage, so no barrier is needed.
+        const int t_last = n_tiles - 1;
+        uint8_t *mine = smem + ((t_last + 1 + wave / 4) % NS) * STAGEB + (wave % 4) * (32 * ROWB);
+        static_assert(STAGEB == 4 * 32 * ROWB && NW <= 8 && NS >= 4, "four waves stage their rows in one ring stage");
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -451,9 +468,28 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
                 uint2 v;
                 v.x = pack_bf16(o_acc[mt][4 * rg + 0] * inv, o_acc[mt][4 * rg + 1] * inv);
                 v.y = pack_bf16(o_acc[mt][4 * rg + 2] * inv, o_acc[mt][4 * rg + 3] * inv);
-                *(uint2 *)(orow + mt * 32 + 8 * rg + 4 * lh) = v;
+                const int chunk = (4 * mt + rg) ^ (li & (CH - 1));
+                *(uint2 *)(mine + li * ROWB + chunk * 16 + lh * 8) = v;
             }
+        // the row index and validity of query row r live in lane r
+        const uint32_t my_row = (uint32_t)part_row;
+        constexpr int ROWS_PER_STORE = 64 / CH;
+#pragma unroll
+        for (int j = 0; j < 32 / ROWS_PER_STORE; ++j) {
+            const int r = j * ROWS_PER_STORE + lane / CH;
+            const int cpos = lane % CH;
+            const uint4 v = *(const uint4 *)(mine + r * ROWB + ((cpos ^ (r & (CH - 1))) * 16));
+            const uint32_t prow = __shfl(my_row, r);
+            const int ok = __shfl((int)q_ok, r);
+            // streaming stores: whole rows that nobody on this compute unit reads again; they leave
+            // the L2 as they are written instead of in one burst when the kernel ends
+            if (ok)
+                __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w},
+                                            (u32x4 *)((uint16_t *)out.o + (size_t)prow * D + cpos * 8));
+        }
+        if (!q_ok) return;
     } else {
+        if (!q_ok) return;
         float *orow = (float *)out.o + part_row * D;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)

@@ -279,16 +279,11 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
     const PT *op = (const PT *)parts.o + prow0 * D + lane * EPL;
     const size_t part_step = (size_t)p.n_tree * D;  // elements between consecutive parts of one row
 
-    // Requests first: the first 64 part LSEs (one per lane) and the first CHUNK split rows.
-    const float l_first = lane < n_cache ? lp[(size_t)lane * p.n_tree] : -INFINITY;
-    typename RP::type raw[CHUNK];
-#pragma unroll
-    for (int k = 0; k < CHUNK; ++k) {
-        const int part = k < n_cache ? k : (n_cache > 0 ? n_cache - 1 : 0);  // clamped: always a valid row
-        if (n_cache > 0) raw[k] = RP::load(op + (size_t)part * part_step);
-    }
-
-    // ---- masked attention over the tree keys (unnormalised, base-2 logits) ----------------
+    // Order of requests (loads return in the order they were issued): the query row and the
+    // mask word first, a short round trip; then the row's first visible tree keys; then the
+    // cached-key partials, by far the most bytes.  The partials are merged among themselves as
+    // they arrive, then the tree keys (long there by then) are worked through, and a two-term
+    // merge of the two results ends the row.
     const T *qrow = (const T *)p.q + b * p.q_stride[0] + h * p.q_stride[1] + i * p.q_stride[2];
     const T *kbase = (const T *)p.k_tree + b * p.kt_stride[0] + g * p.kt_stride[1] + lane * EPL;
     const T *vbase = (const T *)p.v_tree + b * p.vt_stride[0] + g * p.vt_stride[1] + lane * EPL;
@@ -300,53 +295,118 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
         qv[e] *= p.scale_log2;
         acc[e] = 0.f;
     }
-    float m_run = -INFINITY, l_run = 0.f;
-    for (int w = 0; mask != nullptr && w < words; ++w) {  // no mask: no tree part, merge only
+    auto mask_word = [&](int w) {
         uint64_t bits = mrow[w];
         if (w == words - 1 && (p.n_tree & 63)) bits &= ((uint64_t)1 << (p.n_tree & 63)) - 1;
-        while (bits) {
-            // up to KB visible keys at a time, all their rows requested before the first is used
-            int idx[KB];
-            typename RT::type kr[KB], vr[KB];
+        return bits;
+    };
+    // up to KB visible keys at a time, all their rows requested before the first is used
+    int idx[KB];
+    typename RT::type kr[KB], vr[KB];
+    auto request_keys = [&](uint64_t &bits, int w) {
 #pragma unroll
-            for (int u = 0; u < KB; ++u) {
-                idx[u] = bits ? (w << 6) + __builtin_ctzll(bits) : -1;
-                bits &= bits - 1;  // 0 stays 0
-                const int j = idx[u] < 0 ? 0 : idx[u];
-                kr[u] = RT::load(kbase + j * p.kt_stride[2]);
-                vr[u] = RT::load(vbase + j * p.vt_stride[2]);
-            }
-#pragma unroll
-            for (int u = 0; u < KB; ++u) {
-                if (idx[u] < 0) break;  // wave-uniform
-                float kv[EPL], vv[EPL];
-                RT::unpack(kr[u], kv);
-                RT::unpack(vr[u], vv);
-                float part = 0.f;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) part += qv[e] * kv[e];
-                const float z = wave_sum(part);
-                const float m_new = fmaxf(m_run, z);
-                const float alpha = exp2f(m_run - m_new);
-                const float pj = exp2f(z - m_new);
-                l_run = l_run * alpha + pj;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * alpha + pj * vv[e];
-                m_run = m_new;
-            }
+        for (int u = 0; u < KB; ++u) {
+            idx[u] = bits ? (w << 6) + __builtin_ctzll(bits) : -1;
+            bits &= bits - 1;  // 0 stays 0
+            const int j = idx[u] < 0 ? 0 : idx[u];
+            kr[u] = RT::load(kbase + j * p.kt_stride[2]);
+            vr[u] = RT::load(vbase + j * p.vt_stride[2]);
         }
+    };
+    float m_run = -INFINITY, l_run = 0.f;
+    auto use_keys = [&]() {
+#pragma unroll
+        for (int u = 0; u < KB; ++u) {
+            if (idx[u] < 0) break;  // wave-uniform
+            float kv[EPL], vv[EPL];
+            RT::unpack(kr[u], kv);
+            RT::unpack(vr[u], vv);
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) part += qv[e] * kv[e];
+            const float z = wave_sum(part);
+            const float m_new = fmaxf(m_run, z);
+            const float alpha = exp2f(m_run - m_new);
+            const float pj = exp2f(z - m_new);
+            l_run = l_run * alpha + pj;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * alpha + pj * vv[e];
+            m_run = m_new;
+        }
+    };
+    uint64_t bits0 = 0;
+    if (mask != nullptr) {  // no mask: no tree part, merge of the cached-key partials only
+        bits0 = mask_word(0);
+        request_keys(bits0, 0);
     }
-    const float lse_tree = l_run > 0.f ? (m_run + log2f(l_run)) * kLn2 : -INFINITY;
+    // the first 64 part LSEs (one per lane) and the first CHUNK split rows
+    const float l_first = lane < n_cache ? lp[(size_t)lane * p.n_tree] : -INFINITY;
+    typename RP::type raw[CHUNK];
+#pragma unroll
+    for (int k = 0; k < CHUNK; ++k) {
+        const int part = k < n_cache ? k : (n_cache > 0 ? n_cache - 1 : 0);  // clamped: always a valid row
+        if (n_cache > 0) raw[k] = RP::load(op + (size_t)part * part_step);
+    }
 
-    // ---- merge --------------------------------------------------------------------------
-    float top = fmaxf(lse_tree, wave_max(l_first));
+    // ---- merge of the cached-key partials among themselves -----------------------------------
+    float top_c = wave_max(l_first);
     for (int s0 = kWave; s0 < n_cache; s0 += kWave) {
         const int s = s0 + lane;
         const float l = s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY;
-        top = fmaxf(top, wave_max(l));
+        top_c = fmaxf(top_c, wave_max(l));
     }
-    T *orow = out + b * os0 + h * os1 + i * os2 + lane * EPL;
     float o[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[e] = 0.f;
+    float w_lane = 0.f;  // this lane's part weights, summed over the 64-part groups
+    if (top_c != -INFINITY) {
+        for (int s0 = 0; s0 < n_cache; s0 += kWave) {
+            const int s = s0 + lane;
+            const float l = s0 == 0 ? l_first : (s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY);
+            const float w = l == -INFINITY ? 0.f : exp2f((l - top_c) * kLog2e);
+            w_lane += w;
+            const int cnt = n_cache - s0 < kWave ? n_cache - s0 : kWave;
+            for (int c0 = 0; c0 < cnt; c0 += CHUNK) {
+                if (s0 + c0 > 0) {
+#pragma unroll
+                    for (int k = 0; k < CHUNK; ++k) {
+                        const int part = s0 + c0 + k < n_cache ? s0 + c0 + k : n_cache - 1;
+                        raw[k] = RP::load(op + (size_t)part * part_step);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < CHUNK; ++k) {
+                    // past the last part the lane weight is 0 (the clamped row was still a valid read);
+                    // empty parts may hold anything, so they are selected out rather than multiplied
+                    const float wk =
+                        __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), c0 + k));
+                    float v[EPL];
+                    RP::unpack(raw[k], v);
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) o[e] += wk > 0.f ? wk * v[e] : 0.f;
+                }
+            }
+        }
+    }
+    const float wsum_c = wave_sum(w_lane);  // 0 if no cached key is visible
+
+    // ---- masked attention over the tree keys (unnormalised, base-2 logits) ----------------
+    if (mask != nullptr) {
+        use_keys();
+        for (int w = 0; w < words; ++w) {
+            uint64_t bits = w == 0 ? bits0 : mask_word(w);
+            while (bits) {
+                request_keys(bits, w);
+                use_keys();
+            }
+        }
+    }
+
+    // ---- the two results, merged by the aggregation rule ----------------------------------------
+    T *orow = out + b * os0 + h * os1 + i * os2 + lane * EPL;
+    const float lse_c = wsum_c > 0.f ? top_c + log2f(wsum_c) * kLn2 : -INFINITY;
+    const float lse_t = l_run > 0.f ? (m_run + log2f(l_run)) * kLn2 : -INFINITY;
+    const float top = fmaxf(lse_c, lse_t);
     if (top == -INFINITY) {  // no visible key at all
 #pragma unroll
         for (int e = 0; e < EPL; ++e) o[e] = 0.f;
@@ -354,44 +414,15 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
         if (lane == 0) lse[row] = -INFINITY;
         return;
     }
-    const float w_tree = l_run > 0.f ? exp2f((lse_tree - top) * kLog2e) : 0.f;
-    const float tree_scale = l_run > 0.f ? w_tree / l_run : 0.f;
+    const float wa = wsum_c > 0.f ? exp2f((lse_c - top) * kLog2e) : 0.f;
+    const float wb = l_run > 0.f ? exp2f((lse_t - top) * kLog2e) : 0.f;
+    const float inv = 1.f / (wa + wb);
+    const float sa = wsum_c > 0.f ? wa * inv / wsum_c : 0.f;
+    const float sb = l_run > 0.f ? wb * inv / l_run : 0.f;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) o[e] = acc[e] * tree_scale;
-    float w_lane = 0.f;  // this lane's part weights, summed over the 64-part groups
-    for (int s0 = 0; s0 < n_cache; s0 += kWave) {
-        const int s = s0 + lane;
-        const float l = s0 == 0 ? l_first : (s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY);
-        const float w = l == -INFINITY ? 0.f : exp2f((l - top) * kLog2e);
-        w_lane += w;
-        const int cnt = n_cache - s0 < kWave ? n_cache - s0 : kWave;
-        for (int c0 = 0; c0 < cnt; c0 += CHUNK) {
-            if (s0 + c0 > 0) {
-#pragma unroll
-                for (int k = 0; k < CHUNK; ++k) {
-                    const int part = s0 + c0 + k < n_cache ? s0 + c0 + k : n_cache - 1;
-                    raw[k] = RP::load(op + (size_t)part * part_step);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < CHUNK; ++k) {
-                // past the last part the lane weight is 0 (the clamped row was still a valid read);
-                // empty parts may hold anything, so they are selected out rather than multiplied
-                const float wk =
-                    __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), c0 + k));
-                float v[EPL];
-                RP::unpack(raw[k], v);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) o[e] += wk > 0.f ? wk * v[e] : 0.f;
-            }
-        }
-    }
-    const float wsum = wave_sum(w_lane) + w_tree;
-    const float inv = 1.f / wsum;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) o[e] *= inv;
+    for (int e = 0; e < EPL; ++e) o[e] = o[e] * sa + acc[e] * sb;
     Piece<EPL>::store(orow, o);
-    if (lane == 0) lse[row] = top + log2f(wsum) * kLn2;
+    if (lane == 0) lse[row] = top + log2f(wa + wb) * kLn2;
 }
 
 hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, const Partials &cache_parts,
