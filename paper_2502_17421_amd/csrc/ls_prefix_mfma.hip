@@ -15,6 +15,14 @@
 // linearly (lane l -> base + 16*l), so the bank swizzle is applied on the global side:
 // the lane that fills LDS slot (row, pos) fetches chunk pos ^ swizzle(row) of that row.
 //
+// Each split walks its tiles starting at tile (split index mod tile count) and wraps around:
+// all workgroups start together, and without this their addresses would differ only by
+// multiples of the split size and crowd a few memory channels.
+//
+// The partial outputs leave through LDS (free by then) as whole 16-byte-per-lane rows with
+// streaming stores; stored straight from the accumulator layout every store would touch 32
+// rows with 16 bytes each.
+//
 // Operand orientation.  Scores are computed transposed, S^T = K Q^T (keys along the MFMA
 // M axis, queries along N).  With the 32x32 accumulator layout a lane then holds, for ONE
 // query (column = lane % 32), 4-key runs of the tile: exactly the per-lane contraction
@@ -408,11 +416,27 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
                      int key0_next) {
         constexpr bool has_next = decltype(has_next_tag)::value;
         if constexpr (has_next) fetch_k(k_next, kt_next, k_frag);
-        second_product(v_frag, p_prev);
         uint32_t p_cur[8];
-        float sum = numerators(s_cur, p_cur);
         floatx16 s_next = s_cur;
-        if constexpr (has_next) s_next = score(k_frag);
+        if constexpr (has_next) {
+            // output-product and score MFMAs alternate, so that no matrix instruction depends on
+            // the one issued just before it
+            bf16x8 pb[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+                pb[a] = __builtin_bit_cast(bf16x8, make_uint4(p_prev[4 * a], p_prev[4 * a + 1], p_prev[4 * a + 2],
+                                                              p_prev[4 * a + 3]));
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
+#pragma unroll
+            for (int i = 0; i < KSTEPS; ++i) {
+                o_acc[i % MT] = mfma32(v_frag[i / MT][i % MT], pb[i / MT], o_acc[i % MT]);
+                s_next = mfma32(k_frag[i], q_reg[i], s_next);
+            }
+        } else {
+            second_product(v_frag, p_prev);
+        }
+        float sum = numerators(s_cur, p_cur);
         fetch_v(v_cur, kt_cur, v_frag);
         if (__any(!(sum < kSumCap))) {  // also catches inf and nan: redo this step on the general path
             raise_reference(s_cur);
