@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # HBM bytes per launch of the cached-key kernel (fetched + written) from the rocprofv3 FETCH_SIZE /
 # WRITE_SIZE runs summarised in profiles/verify_call_C3_mi355x.md, scaled by the copy calibration.
 # They cannot be read while this script runs; None for workloads without a committed profile.
-MEASURED_TRAFFIC_BYTES = {"C3": 138632880 + 17039634}
+MEASURED_TRAFFIC_BYTES = {"C3": 138653109 + 17118618}
 
 
 def algorithmic_bytes_prefix(w, prefix_lens):
