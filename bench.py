@@ -34,7 +34,7 @@ MEASURED_TRAFFIC_BYTES = {"C3": 138653109 + 17118618}
 def algorithmic_bytes_prefix(w, prefix_lens):
     """Bytes the cached-key kernel must move per launch: K and V rows of every KV head once,
     plus the queries.  Split partials are overhead and not counted."""
-    e = 2 if w.dtype == "bf16" else 4
+    e = 4 if w.dtype == "f32" else 2
     total = 0
     for p in prefix_lens:
         total += 2 * w.n_kv_heads * int(p) * w.head_dim * e + w.n_q_heads * w.n_tree * w.head_dim * e
@@ -42,7 +42,7 @@ def algorithmic_bytes_prefix(w, prefix_lens):
 
 
 def algorithmic_bytes_call(w, prefix_lens):
-    e = 2 if w.dtype == "bf16" else 4
+    e = 4 if w.dtype == "f32" else 2
     total = 0
     for p in prefix_lens:
         total += (2 * w.n_kv_heads * int(p) * w.head_dim * e + 2 * w.n_kv_heads * w.n_tree * w.head_dim * e +
@@ -65,8 +65,8 @@ def bench_accept_commit(args, w):
     from paper_2502_17421_amd import synth
 
     rng = np.random.default_rng(w.seed)
-    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
-    e = 2 if w.dtype == "bf16" else 4
+    dt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.dtype]
+    e = 4 if w.dtype == "f32" else 2
     cap = w.prefix_hi + w.n_tree
     parents, draft, target, plens = [], [], [], []
     for b in range(w.batch):
@@ -215,7 +215,7 @@ def main():
     # split count, partials in the problem's dtype): HIP events on its stream around the whole
     # timed region of back-to-back launches, so the per-launch figure excludes the ~6 us that an
     # event pair around a single launch adds on this stack
-    part_dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    part_dt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.dtype]
     o_part = torch.empty((w.batch, w.n_q_heads, n_splits, w.n_tree, w.head_dim), dtype=part_dt, device="cuda")
     l_part = torch.empty((w.batch, w.n_q_heads, n_splits, w.n_tree), dtype=torch.float32, device="cuda")
 
@@ -256,7 +256,7 @@ def main():
     fl = flops_prefix(w, plens)
     t_hbm = bytes_prefix / (HBM_PEAK_GBS * 1e9) * 1e6
     t_mfma = fl / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6
-    if w.dtype == "bf16" and t_mfma > t_hbm:
+    if w.dtype != "f32" and t_mfma > t_hbm:
         roof = {"bound": "mfma", "achieved": fl / kernel_us / 1e6, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     else:
         roof = {"bound": "hbm", "achieved": bytes_prefix / kernel_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}

@@ -43,7 +43,8 @@
  *   lse      [batch, n_q_heads,  n_tree]                  float, contiguous
  * Query head h reads KV head h / (n_q_heads / n_kv_heads).
  *
- * Supported: dtype bf16 or f32; head_dim 64 or 128; 1 <= n_tree <= 128;
+ * Supported: dtype bf16, f16 (the precision of the paper's experiments, appendix
+ * "Experiments Details") or f32; head_dim 64 or 128; 1 <= n_tree <= 128;
  * n_q_heads a multiple of n_kv_heads; 0 <= prefix length <= max_prefix_len.
  * Anything else returns LS_ERR_UNSUPPORTED.
  */
@@ -61,7 +62,7 @@ typedef enum {
     LS_OK = 0,
     LS_ERR_NULL = -1,        /* a required pointer is NULL */
     LS_ERR_SHAPE = -2,       /* a size is non-positive or inconsistent */
-    LS_ERR_DTYPE = -3,       /* dtype is not LS_BF16 / LS_F32 */
+    LS_ERR_DTYPE = -3,       /* dtype is not LS_BF16 / LS_F16 / LS_F32 */
     LS_ERR_STRIDE = -4,      /* a stride or pointer breaks the 16-byte row alignment */
     LS_ERR_TREE = -5,        /* parents is not a topologically ordered forest */
     LS_ERR_WORKSPACE = -6,   /* workspace missing, misaligned or too small */
@@ -69,7 +70,7 @@ typedef enum {
     LS_ERR_UNSUPPORTED = -8  /* valid request outside the supported set */
 } ls_status;
 
-typedef enum { LS_BF16 = 0, LS_F32 = 1 } ls_dtype;
+typedef enum { LS_BF16 = 0, LS_F32 = 1, LS_F16 = 2 } ls_dtype;
 
 #define LS_MAX_TREE 128
 
@@ -125,7 +126,7 @@ int ls_workspace_bytes(const ls_desc *desc, size_t *bytes_out);
 /*
  * The whole path (Section 3.3): tree mask from `parents`, split-KV attention over the
  * cache, masked attention over the tree tokens, log-sum-exp merge into out / lse.  For
- * bf16 problems it runs as two launches: the cached-key kernel (whose last workgroups also
+ * bf16 and f16 problems it runs as two launches: the cached-key kernel (whose last workgroups also
  * build the mask), then one kernel that does the tree attention and the merge per row.
  *
  *   prefix_lens  DEVICE int32[batch]; values are clamped into [0, max_prefix_len].
@@ -185,8 +186,8 @@ int ls_build_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree,
  * n_splits (ls_prefix_split_len).  An empty split writes lse = -inf and leaves its output
  * rows untouched.
  *   n_splits    >= 1, or 0 for the library's choice (ls_prefix_num_splits)
- *   part_dtype  storage type of o_part: LS_F32, or LS_BF16 when desc->dtype is LS_BF16
- *               (what ls_hybrid_tree_attn uses internally for bf16 problems)
+ *   part_dtype  storage type of o_part: LS_F32, or desc->dtype itself when that is LS_BF16 or
+ *               LS_F16 (what ls_hybrid_tree_attn uses internally for 16-bit problems)
  *   o_part      DEVICE part_dtype[batch, n_q_heads, n_splits, n_tree, head_dim], normalised
  *   lse_part    DEVICE float[batch, n_q_heads, n_splits, n_tree], natural log
  */
@@ -213,7 +214,7 @@ int ls_tree_attn_masked(const ls_desc *desc, const void *q,
  * (d) Log-sum-exp merge of n_parts partial results per query row (Section 3.3
  * "Aggregation", applied associatively).  Parts with lse = -inf are skipped, whatever
  * their output rows hold; if every part is empty the row gets lse = -inf and zeros.
- *   part_dtype storage type of o_parts: LS_F32 or LS_BF16
+ *   part_dtype storage type of o_parts: LS_F32, or desc->dtype when that is LS_BF16 / LS_F16
  *   o_parts    DEVICE part_dtype[batch, n_q_heads, n_parts, n_tree, head_dim]
  *   lse_parts  DEVICE float[batch, n_q_heads, n_parts, n_tree]
  *   out        DEVICE dtype, strided by desc->o_stride;  lse DEVICE float[batch,n_q_heads,n_tree]

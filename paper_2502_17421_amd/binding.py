@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libls_attn.so")
 LS_OK = 0
 LS_ERR_NULL, LS_ERR_SHAPE, LS_ERR_DTYPE, LS_ERR_STRIDE = -1, -2, -3, -4
 LS_ERR_TREE, LS_ERR_WORKSPACE, LS_ERR_HIP, LS_ERR_UNSUPPORTED = -5, -6, -7, -8
-LS_BF16, LS_F32 = 0, 1
+LS_BF16, LS_F32, LS_F16 = 0, 1, 2
 LS_MAX_TREE = 128
 
 _i32, _i64, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_float
@@ -104,6 +104,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return LS_BF16
     if t.dtype == torch.float32:
         return LS_F32
+    if t.dtype == torch.float16:
+        return LS_F16
     return -1
 
 
@@ -214,7 +216,8 @@ def ls_build_tree_mask(parents, mask, err_flag=None, stream=None, check: bool = 
 
 def ls_prefix_attn_splitkv(desc, q, k_cache, v_cache, prefix_lens, n_splits, o_part, lse_part, stream=None,
                            check: bool = True) -> int:
-    """o_part: float32 or bfloat16 tensor [B,Hq,n_splits,T,D]; its dtype selects part_dtype."""
+    """o_part: float32 tensor, or a tensor of the problem's own 16-bit type, [B,Hq,n_splits,T,D]; its dtype selects
+    part_dtype."""
     st = lib().ls_prefix_attn_splitkv(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(prefix_lens),
                                       int(n_splits), _dtype_code(o_part), _ptr(o_part), _ptr(lse_part),
                                       _stream(stream))

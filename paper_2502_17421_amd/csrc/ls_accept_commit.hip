@@ -164,7 +164,7 @@ hipError_t launch_kv_commit(const Problem &p, int dtype, const int32_t *accept_p
                             void *k_cache, void *v_cache, int32_t *new_prefix_lens, int32_t *err_flag,
                             hipStream_t stream)
 {
-    const int elem_bytes = dtype == LS_BF16 ? 2 : 4;
+    const int elem_bytes = is_16bit(dtype) ? 2 : 4;
     hipLaunchKernelGGL(kv_commit_kernel, dim3(p.batch * p.n_kv_heads), dim3(256), 0, stream, p, elem_bytes,
                        accept_path, accept_len, (uint8_t *)k_cache, (uint8_t *)v_cache, new_prefix_lens, err_flag);
     return hipGetLastError();

@@ -12,7 +12,7 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-inline size_t elem_size(int dtype) { return dtype == LS_BF16 ? 2 : 4; }
+inline size_t elem_size(int dtype) { return is_16bit(dtype) ? 2 : 4; }
 
 int check_stride(const int64_t s[3], int head_dim, size_t esz, bool is_output)
 {
@@ -32,7 +32,7 @@ int validate(const ls_desc *d)
         d->max_prefix_len < 0)
         return LS_ERR_SHAPE;
     if (d->n_q_heads % d->n_kv_heads != 0) return LS_ERR_SHAPE;
-    if (d->dtype != LS_BF16 && d->dtype != LS_F32) return LS_ERR_DTYPE;
+    if (d->dtype != LS_BF16 && d->dtype != LS_F32 && d->dtype != LS_F16) return LS_ERR_DTYPE;
     if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return LS_ERR_SHAPE;
     if (d->head_dim != 64 && d->head_dim != 128) return LS_ERR_UNSUPPORTED;
     if (d->n_tree > LS_MAX_TREE) return LS_ERR_UNSUPPORTED;
@@ -131,11 +131,11 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
     if (s <= 0) {
         const int group = d.n_q_heads / d.n_kv_heads;
         const int rows_kv = group * d.n_tree;
-        const int rows_wg = d.dtype == LS_BF16 ? 256 : 32;
+        const int rows_wg = is_16bit(d.dtype) ? 256 : 32;
         const int64_t units = (int64_t)d.batch * d.n_kv_heads * ((rows_kv + rows_wg - 1) / rows_wg);
         const int cus = compute_units();
         // at least four key tiles per split on the MFMA path; the float path has 32-key tiles
-        int64_t s_max = max_p / (d.dtype == LS_BF16 ? 4 * kTile : kTile);
+        int64_t s_max = max_p / (is_16bit(d.dtype) ? 4 * kTile : kTile);
         if (s_max > 64) s_max = 64;
         if (s_max < 1) s_max = 1;
         double best = 0.0;
@@ -256,14 +256,14 @@ int ls_prefix_attn_splitkv(const ls_desc *desc, const void *q, const void *k_cac
     if (!q || !prefix_lens || !o_part || !lse_part) return LS_ERR_NULL;
     if (desc->max_prefix_len > 0 && (!k_cache || !v_cache)) return LS_ERR_NULL;
     if (n_splits < 0 || n_splits > 65535) return LS_ERR_SHAPE;
-    if (part_dtype != LS_F32 && part_dtype != LS_BF16) return LS_ERR_DTYPE;
+    if (part_dtype != LS_F32 && !(is_16bit(part_dtype) && part_dtype == desc->dtype)) return LS_ERR_DTYPE;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o_part)) return LS_ERR_STRIDE;
     const SplitPlan plan = plan_splits(*desc, n_splits);
     const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, nullptr, nullptr);
-    const Partials out{o_part, lse_part, plan.n_splits, 0, part_dtype == LS_BF16};
+    const Partials out{o_part, lse_part, plan.n_splits, 0, is_16bit(part_dtype)};
     hipError_t e;
     if (prefix_mfma_supports(p, desc->dtype)) {
-        e = launch_prefix_mfma(p, plan, out, MaskJob{nullptr, nullptr, nullptr}, (hipStream_t)stream);
+        e = launch_prefix_mfma(p, desc->dtype, plan, out, MaskJob{nullptr, nullptr, nullptr}, (hipStream_t)stream);
     } else {
         if (part_dtype != LS_F32) return LS_ERR_UNSUPPORTED;
         e = launch_prefix_valu(p, desc->dtype, plan, out, (hipStream_t)stream);
@@ -290,10 +290,10 @@ int ls_lse_merge(const ls_desc *desc, int32_t n_parts, int32_t part_dtype, const
     if (rc) return rc;
     if (!o_parts || !lse_parts || !out || !lse) return LS_ERR_NULL;
     if (n_parts <= 0) return LS_ERR_SHAPE;
-    if (part_dtype != LS_F32 && part_dtype != LS_BF16) return LS_ERR_DTYPE;
+    if (part_dtype != LS_F32 && !(is_16bit(part_dtype) && part_dtype == desc->dtype)) return LS_ERR_DTYPE;
     if (!aligned16(o_parts) || !aligned16(out)) return LS_ERR_STRIDE;
     return launch_merge(desc->batch, desc->n_q_heads, desc->n_tree, desc->head_dim, desc->dtype, n_parts, o_parts,
-                        part_dtype == LS_BF16, lse_parts, out, desc->o_stride, lse, (hipStream_t)stream) == hipSuccess
+                        is_16bit(part_dtype), lse_parts, out, desc->o_stride, lse, (hipStream_t)stream) == hipSuccess
                ? LS_OK
                : LS_ERR_HIP;
 }
@@ -324,12 +324,12 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache,
 
     // (b) cached keys -> parts [0, n_splits), stored in the problem's dtype; on the MFMA path
     // the same launch carries the workgroups of (a), the tree mask
-    const Partials cache_out{o_parts, lse_parts, w.n_parts, 0, desc->dtype == LS_BF16};
+    const Partials cache_out{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype)};
     if (prefix_mfma_supports(p, desc->dtype)) {
-        if (launch_prefix_mfma(p, plan, cache_out, MaskJob{parents, mask, err}, s) != hipSuccess) return LS_ERR_HIP;
+        if (launch_prefix_mfma(p, desc->dtype, plan, cache_out, MaskJob{parents, mask, err}, s) != hipSuccess) return LS_ERR_HIP;
     } else {
         const Partials f32_out{o_parts, lse_parts, w.n_parts, 0, 0};
-        if (desc->dtype == LS_BF16) return LS_ERR_UNSUPPORTED;  // bf16 row strides beyond the MFMA kernel's range
+        if (is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;  // 16-bit row strides beyond the MFMA kernel's range
         if (launch_prefix_valu(p, desc->dtype, plan, f32_out, s) != hipSuccess) return LS_ERR_HIP;
         if (launch_tree_mask(parents, desc->batch, desc->n_tree, mask, err, s) != hipSuccess) return LS_ERR_HIP;
     }
@@ -357,9 +357,9 @@ int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const
     hipStream_t s = (hipStream_t)stream;
     const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, nullptr, nullptr);
     const bool mfma = prefix_mfma_supports(p, desc->dtype);
-    if (!mfma && desc->dtype == LS_BF16) return LS_ERR_UNSUPPORTED;
-    const Partials parts{o_parts, lse_parts, w.n_parts, 0, desc->dtype == LS_BF16};
-    const hipError_t e = mfma ? launch_prefix_mfma(p, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s)
+    if (!mfma && is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;
+    const Partials parts{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype)};
+    const hipError_t e = mfma ? launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s)
                               : launch_prefix_valu(p, desc->dtype, plan, parts, s);
     if (e != hipSuccess) return LS_ERR_HIP;
     // the tail kernel without a mask: merge of the split partials only

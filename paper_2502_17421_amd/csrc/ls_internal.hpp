@@ -27,14 +27,14 @@ struct Problem {
 };
 
 // Where partial results go: o [batch, n_q_heads, parts_stride, n_tree, head_dim] in float or
-// bf16 (o_is_bf16), lse [batch, n_q_heads, parts_stride, n_tree] float.  A producer writes
-// parts [part_base, part_base + its own count).
+// in the problem's 16-bit type (o_is_16bit), lse [batch, n_q_heads, parts_stride, n_tree]
+// float.  A producer writes parts [part_base, part_base + its own count).
 struct Partials {
     void *o;
     float *lse;
     int32_t parts_stride;
     int32_t part_base;
-    int32_t o_is_bf16;
+    int32_t o_is_16bit;
 };
 
 // Work appended to the cached-key launch so that the whole call needs one launch less:
@@ -60,6 +60,14 @@ __device__ __forceinline__ uint16_t float_to_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
+// Element type tags: float, uint16_t (a bf16 bit pattern) and half_t (an IEEE half bit pattern).
+struct half_t {
+    uint16_t bits;
+};
+__device__ __forceinline__ float half_to_float(uint16_t v) { return (float)__builtin_bit_cast(_Float16, v); }
+__device__ __forceinline__ uint16_t float_to_half(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+inline bool is_16bit(int dtype) { return dtype == LS_BF16 || dtype == LS_F16; }
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float *p) { return *p; }
@@ -68,6 +76,11 @@ template <> struct Elem<float> {
 template <> struct Elem<uint16_t> {
     static __device__ __forceinline__ float load(const uint16_t *p) { return bf16_to_float(*p); }
     static __device__ __forceinline__ void store(uint16_t *p, float v) { *p = float_to_bf16(v); }
+};
+
+template <> struct Elem<half_t> {
+    static __device__ __forceinline__ float load(const half_t *p) { return half_to_float(p->bits); }
+    static __device__ __forceinline__ void store(half_t *p, float v) { p->bits = float_to_half(v); }
 };
 
 __device__ __forceinline__ float wave_sum(float v)
@@ -119,12 +132,12 @@ hipError_t launch_tree_attn(const Problem &p, int dtype, const uint64_t *mask, c
                             hipStream_t stream);
 hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
                               hipStream_t stream);
-hipError_t launch_prefix_mfma(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
-                              hipStream_t stream);
+hipError_t launch_prefix_mfma(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
+                              const MaskJob &mask_job, hipStream_t stream);
 bool prefix_mfma_supports(const Problem &p, int dtype);
 SplitPlan plan_splits(const ls_desc &d, int32_t n_splits_request);
 hipError_t launch_merge(int32_t batch, int32_t n_q_heads, int32_t n_tree, int32_t head_dim, int dtype,
-                        int32_t n_parts, const void *o_parts, int parts_are_bf16, const float *lse_parts, void *out,
+                        int32_t n_parts, const void *o_parts, int parts_are_16bit, const float *lse_parts, void *out,
                         const int64_t o_stride[3], float *lse, hipStream_t stream);
 // Masked tree attention and the merge with n_cache_parts cached-key partials in one kernel.
 hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, const Partials &cache_parts,

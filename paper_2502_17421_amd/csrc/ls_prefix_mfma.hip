@@ -55,7 +55,8 @@ namespace ls {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));  // also carries eight IEEE halves as bit patterns
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
@@ -65,20 +66,40 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int TK = 64;              // keys per LDS stage
 constexpr int SUB = 32;             // keys per softmax step (one MFMA row tile)
 constexpr float kLazy = 8.f;        // general path: m is raised only when a score exceeds it by 2^8
-constexpr float kSumCap = 0x1p40f;  // common path: largest row-sum increment taken without raising m
+// common path: largest row-sum increment taken without raising m; the numerators are stored in
+// the operand type, and a half holds nothing above 65504
+template <bool F16> constexpr float kSumCap = F16 ? 0x1p15f : 0x1p40f;
 
 #define LS_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 
-__device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c)
+template <bool F16> __device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c)
 {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, a), __builtin_bit_cast(halfx8, b), c,
+                                                      0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+// two floats to one register of the operand type, round to nearest even
+template <bool F16> __device__ __forceinline__ uint32_t pack16(float lo, float hi)
 {
     floatx2 f = {lo, hi};
-    bf16x2 b = __builtin_convertvector(f, bf16x2);
-    return __builtin_bit_cast(uint32_t, b);
+    if constexpr (F16) {
+        typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, halfx2));
+    } else {
+        bf16x2 b = __builtin_convertvector(f, bf16x2);
+        return __builtin_bit_cast(uint32_t, b);
+    }
+}
+// the softmax numerators: one instruction per pair in either type (halves round toward zero,
+// a bias of 2^-12 of the value that the fp32 row sums do not share; far below the output's
+// own rounding)
+template <bool F16> __device__ __forceinline__ uint32_t pack_numerators(float lo, float hi)
+{
+    if constexpr (F16) return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+    else return pack16<false>(lo, hi);
 }
 
 // max / sum across the two 32-lane halves of the wave (lane l with lane l ^ 32)
@@ -133,7 +154,7 @@ __device__ __forceinline__ int vswz(int row)
 
 }  // namespace
 
-template <int D, int NW, int NS>
+template <int D, int NW, int NS, bool F16>
 __global__ void __launch_bounds__(NW * 64)
 prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, int32_t n_qblocks)
 {
@@ -334,7 +355,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) s_acc = mfma32(kf[kk], q_reg[kk], s_acc);
+        for (int kk = 0; kk < KSTEPS; ++kk) s_acc = mfma32<F16>(kf[kk], q_reg[kk], s_acc);
         return s_acc;
     };
     auto second_product = [&](const bf16x8 (&vf)[2][MT], const uint32_t (&pp)[8]) {  // O^T += V^T P^T
@@ -343,7 +364,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
             const bf16x8 pb =
                 __builtin_bit_cast(bf16x8, make_uint4(pp[4 * a], pp[4 * a + 1], pp[4 * a + 2], pp[4 * a + 3]));
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) o_acc[mt] = mfma32(vf[a][mt], pb, o_acc[mt]);
+            for (int mt = 0; mt < MT; ++mt) o_acc[mt] = mfma32<F16>(vf[a][mt], pb, o_acc[mt]);
         }
     };
     auto mask_tail = [&](floatx16 &s_acc, int key0) {  // keys past the end of the split weigh nothing
@@ -362,7 +383,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
         for (int r = 0; r < 16; r += 2) {
             const float p0 = __builtin_amdgcn_exp2f(s_acc[r] * c - mc);
             const float p1 = __builtin_amdgcn_exp2f(s_acc[r + 1] * c - mc);
-            pp[r >> 1] = pack_bf16(p0, p1);
+            pp[r >> 1] = pack_numerators<F16>(p0, p1);
             sum += p0 + p1;
         }
         return sum;
@@ -430,15 +451,15 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
             for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
 #pragma unroll
             for (int i = 0; i < KSTEPS; ++i) {
-                o_acc[i % MT] = mfma32(v_frag[i / MT][i % MT], pb[i / MT], o_acc[i % MT]);
-                s_next = mfma32(k_frag[i], q_reg[i], s_next);
+                o_acc[i % MT] = mfma32<F16>(v_frag[i / MT][i % MT], pb[i / MT], o_acc[i % MT]);
+                s_next = mfma32<F16>(k_frag[i], q_reg[i], s_next);
             }
         } else {
             second_product(v_frag, p_prev);
         }
         float sum = numerators(s_cur, p_cur);
         fetch_v(v_cur, kt_cur, v_frag);
-        if (__any(!(sum < kSumCap))) {  // also catches inf and nan: redo this step on the general path
+        if (__any(!(sum < kSumCap<F16>))) {  // also catches inf and nan: redo this step on the general path
             raise_reference(s_cur);
             sum = numerators(s_cur, p_cur);
         }
@@ -475,7 +496,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     // ---- epilogue: normalise and store this split's partial result -----------------------
     const float l_tot = half_sum(l_run);
     const float inv = 1.f / l_tot;
-    if (out.o_is_bf16) {
+    if (out.o_is_16bit) {
         // A lane holds 4-element runs of one query row, 256 bytes apart from its neighbours':
         // stored as they are, every store instruction would touch 32 rows with 16 bytes each.
         // The rows go through LDS instead and leave as whole rows, 16 bytes per lane.  The
@@ -490,8 +511,8 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 uint2 v;
-                v.x = pack_bf16(o_acc[mt][4 * rg + 0] * inv, o_acc[mt][4 * rg + 1] * inv);
-                v.y = pack_bf16(o_acc[mt][4 * rg + 2] * inv, o_acc[mt][4 * rg + 3] * inv);
+                v.x = pack16<F16>(o_acc[mt][4 * rg + 0] * inv, o_acc[mt][4 * rg + 1] * inv);
+                v.y = pack16<F16>(o_acc[mt][4 * rg + 2] * inv, o_acc[mt][4 * rg + 3] * inv);
                 const int chunk = (4 * mt + rg) ^ (li & (CH - 1));
                 *(uint2 *)(mine + li * ROWB + chunk * 16 + lh * 8) = v;
             }
@@ -534,19 +555,19 @@ bool prefix_mfma_supports(const Problem &p, int dtype)
 {
     // the tile loads address rows of one tile with 32-bit byte offsets
     const int64_t max_row_bytes = 2 * (p.kc_stride[2] > p.vc_stride[2] ? p.kc_stride[2] : p.vc_stride[2]);
-    return dtype == LS_BF16 && (p.head_dim == 128 || p.head_dim == 64) && max_row_bytes * TK < (1ll << 31);
+    return is_16bit(dtype) && (p.head_dim == 128 || p.head_dim == 64) && max_row_bytes * TK < (1ll << 31);
 }
 
 namespace {
 
-template <int D, int NW, int NS>
+template <int D, int NW, int NS, bool F16>
 hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
                       hipStream_t stream)
 {
     constexpr int lds_bytes = NS * 2 * TK * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a compute unit");
     static_assert(NW * 64 >= LS_MAX_TREE, "the mask workgroups need one thread per tree token");
-    auto kernel = prefix_mfma_kernel<D, NW, NS>;
+    auto kernel = prefix_mfma_kernel<D, NW, NS, F16>;
     static hipError_t attr = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  lds_bytes);
     if (attr != hipSuccess) return attr;
@@ -563,18 +584,17 @@ hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &o
 
 }  // namespace
 
-hipError_t launch_prefix_mfma(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
-                              hipStream_t stream)
+hipError_t launch_prefix_mfma(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
+                              const MaskJob &mask_job, hipStream_t stream)
 {
     const int rows_kv = p.group * p.n_tree;
-    if (p.head_dim == 128) {
-        if (rows_kv > 128) return launch_one<128, 8, 4>(p, plan, out, mask_job, stream);
-        return launch_one<128, 4, 4>(p, plan, out, mask_job, stream);
-    }
-    if (p.head_dim == 64) {
-        if (rows_kv > 128) return launch_one<64, 8, 4>(p, plan, out, mask_job, stream);
-        return launch_one<64, 4, 4>(p, plan, out, mask_job, stream);
-    }
+    const bool f16 = dtype == LS_F16;
+#define LS_MFMA_CASE(DD, WW)                                                              \
+    (f16 ? launch_one<DD, WW, 4, true>(p, plan, out, mask_job, stream)                   \
+         : launch_one<DD, WW, 4, false>(p, plan, out, mask_job, stream))
+    if (p.head_dim == 128) return rows_kv > 128 ? LS_MFMA_CASE(128, 8) : LS_MFMA_CASE(128, 4);
+    if (p.head_dim == 64) return rows_kv > 128 ? LS_MFMA_CASE(64, 8) : LS_MFMA_CASE(64, 4);
+#undef LS_MFMA_CASE
     return hipErrorInvalidValue;
 }
 

@@ -22,6 +22,12 @@ __device__ __forceinline__ float4 load4(const uint16_t *p)
     return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
                        __uint_as_float(v.y & 0xffff0000u));
 }
+__device__ __forceinline__ float4 load4(const half_t *p)
+{
+    const uint2 v = *(const uint2 *)p;
+    return make_float4(half_to_float((uint16_t)v.x), half_to_float((uint16_t)(v.x >> 16)),
+                       half_to_float((uint16_t)v.y), half_to_float((uint16_t)(v.y >> 16)));
+}
 }
 
 template <typename T, int D>
@@ -198,6 +204,8 @@ hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan
 #define LS_PV_CASE(T, DD) hipLaunchKernelGGL((prefix_valu_kernel<T, DD>), grid, block, 0, stream, p, plan, out)
     if (dtype == LS_BF16 && p.head_dim == 128) LS_PV_CASE(uint16_t, 128);
     else if (dtype == LS_BF16 && p.head_dim == 64) LS_PV_CASE(uint16_t, 64);
+    else if (dtype == LS_F16 && p.head_dim == 128) LS_PV_CASE(half_t, 128);
+    else if (dtype == LS_F16 && p.head_dim == 64) LS_PV_CASE(half_t, 64);
     else if (dtype == LS_F32 && p.head_dim == 128) LS_PV_CASE(float, 128);
     else if (dtype == LS_F32 && p.head_dim == 64) LS_PV_CASE(float, 64);
     else return hipErrorInvalidValue;

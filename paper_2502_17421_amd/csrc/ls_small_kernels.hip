@@ -95,6 +95,8 @@ hipError_t launch_tree_attn(const Problem &p, int dtype, const uint64_t *mask, c
     hipLaunchKernelGGL((tree_attn_kernel<T, DD>), grid, block, 0, stream, p, mask, out)
     if (dtype == LS_BF16 && p.head_dim == 128) LS_TREE_CASE(uint16_t, 128);
     else if (dtype == LS_BF16 && p.head_dim == 64) LS_TREE_CASE(uint16_t, 64);
+    else if (dtype == LS_F16 && p.head_dim == 128) LS_TREE_CASE(half_t, 128);
+    else if (dtype == LS_F16 && p.head_dim == 64) LS_TREE_CASE(half_t, 64);
     else if (dtype == LS_F32 && p.head_dim == 128) LS_TREE_CASE(float, 128);
     else if (dtype == LS_F32 && p.head_dim == 64) LS_TREE_CASE(float, 64);
     else return hipErrorInvalidValue;
@@ -113,6 +115,13 @@ __device__ __forceinline__ float4 load4(const uint16_t *p)
     const uint2 v = *(const uint2 *)p;
     return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
                        __uint_as_float(v.y & 0xffff0000u));
+}
+
+__device__ __forceinline__ float4 load4(const half_t *p)
+{
+    const uint2 v = *(const uint2 *)p;
+    return make_float4(half_to_float((uint16_t)v.x), half_to_float((uint16_t)(v.x >> 16)),
+                       half_to_float((uint16_t)v.y), half_to_float((uint16_t)(v.y >> 16)));
 }
 
 template <typename T, typename PT, int D>
@@ -159,7 +168,7 @@ merge_kernel(int32_t rows_total, int32_t n_q_heads, int32_t n_tree, int32_t n_pa
 }
 
 hipError_t launch_merge(int32_t batch, int32_t n_q_heads, int32_t n_tree, int32_t head_dim, int dtype,
-                        int32_t n_parts, const void *o_parts, int parts_are_bf16, const float *lse_parts, void *out,
+                        int32_t n_parts, const void *o_parts, int parts_are_16bit, const float *lse_parts, void *out,
                         const int64_t o_stride[3], float *lse, hipStream_t stream)
 {
     const int rows = batch * n_q_heads * n_tree;
@@ -168,17 +177,30 @@ hipError_t launch_merge(int32_t batch, int32_t n_q_heads, int32_t n_tree, int32_
 #define LS_MERGE_CASE(T, PT, DD)                                                                              \
     hipLaunchKernelGGL((merge_kernel<T, PT, DD>), grid, block, 0, stream, rows, n_q_heads, n_tree, n_parts,     \
                        (const PT *)o_parts, lse_parts, (T *)out, o_stride[0], o_stride[1], o_stride[2], lse)
-    const int key = (dtype == LS_BF16 ? 0 : 1) | (parts_are_bf16 ? 2 : 0) | (head_dim == 128 ? 4 : 0);
     if (head_dim != 64 && head_dim != 128) return hipErrorInvalidValue;
-    switch (key) {
-    case 0: LS_MERGE_CASE(uint16_t, float, 64); break;
-    case 1: LS_MERGE_CASE(float, float, 64); break;
-    case 2: LS_MERGE_CASE(uint16_t, uint16_t, 64); break;
-    case 3: LS_MERGE_CASE(float, uint16_t, 64); break;
-    case 4: LS_MERGE_CASE(uint16_t, float, 128); break;
-    case 5: LS_MERGE_CASE(float, float, 128); break;
-    case 6: LS_MERGE_CASE(uint16_t, uint16_t, 128); break;
-    default: LS_MERGE_CASE(float, uint16_t, 128); break;
+    // parts are float, or 16-bit parts of a 16-bit problem in the problem's own type
+    if (dtype == LS_F32) {
+        if (parts_are_16bit) return hipErrorInvalidValue;
+        if (head_dim == 128) LS_MERGE_CASE(float, float, 128);
+        else LS_MERGE_CASE(float, float, 64);
+    } else if (dtype == LS_BF16) {
+        if (parts_are_16bit) {
+            if (head_dim == 128) LS_MERGE_CASE(uint16_t, uint16_t, 128);
+            else LS_MERGE_CASE(uint16_t, uint16_t, 64);
+        } else {
+            if (head_dim == 128) LS_MERGE_CASE(uint16_t, float, 128);
+            else LS_MERGE_CASE(uint16_t, float, 64);
+        }
+    } else if (dtype == LS_F16) {
+        if (parts_are_16bit) {
+            if (head_dim == 128) LS_MERGE_CASE(half_t, half_t, 128);
+            else LS_MERGE_CASE(half_t, half_t, 64);
+        } else {
+            if (head_dim == 128) LS_MERGE_CASE(half_t, float, 128);
+            else LS_MERGE_CASE(half_t, float, 64);
+        }
+    } else {
+        return hipErrorInvalidValue;
     }
 #undef LS_MERGE_CASE
     return hipGetLastError();
@@ -195,6 +217,8 @@ template <> struct Piece<1> {
     static __device__ __forceinline__ void load(const uint16_t *p, float *v) { v[0] = bf16_to_float(p[0]); }
     static __device__ __forceinline__ void store(float *p, const float *v) { p[0] = v[0]; }
     static __device__ __forceinline__ void store(uint16_t *p, const float *v) { p[0] = float_to_bf16(v[0]); }
+    static __device__ __forceinline__ void load(const half_t *p, float *v) { v[0] = half_to_float(p[0].bits); }
+    static __device__ __forceinline__ void store(half_t *p, const float *v) { p[0].bits = float_to_half(v[0]); }
 };
 template <> struct Piece<2> {
     static __device__ __forceinline__ void load(const float *p, float *v)
@@ -213,6 +237,16 @@ template <> struct Piece<2> {
     static __device__ __forceinline__ void store(uint16_t *p, const float *v)
     {
         *(uint32_t *)p = (uint32_t)float_to_bf16(v[0]) | ((uint32_t)float_to_bf16(v[1]) << 16);
+    }
+    static __device__ __forceinline__ void load(const half_t *p, float *v)
+    {
+        const uint32_t t = *(const uint32_t *)p;
+        v[0] = half_to_float((uint16_t)t);
+        v[1] = half_to_float((uint16_t)(t >> 16));
+    }
+    static __device__ __forceinline__ void store(half_t *p, const float *v)
+    {
+        *(uint32_t *)p = (uint32_t)float_to_half(v[0]) | ((uint32_t)float_to_half(v[1]) << 16);
     }
 };
 
@@ -251,6 +285,21 @@ template <> struct Raw<uint16_t, 2> {
     {
         v[0] = __uint_as_float(r << 16);
         v[1] = __uint_as_float(r & 0xffff0000u);
+    }
+};
+
+template <> struct Raw<half_t, 1> {
+    typedef uint16_t type;
+    static __device__ __forceinline__ type load(const half_t *p) { return p->bits; }
+    static __device__ __forceinline__ void unpack(type r, float *v) { v[0] = half_to_float(r); }
+};
+template <> struct Raw<half_t, 2> {
+    typedef uint32_t type;
+    static __device__ __forceinline__ type load(const half_t *p) { return *(const uint32_t *)p; }
+    static __device__ __forceinline__ void unpack(type r, float *v)
+    {
+        v[0] = half_to_float((uint16_t)r);
+        v[1] = half_to_float((uint16_t)(r >> 16));
     }
 };
 
@@ -441,15 +490,23 @@ hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, 
     } while (0)
     if (p.head_dim != 64 && p.head_dim != 128) return hipErrorInvalidValue;
     if (dtype == LS_BF16) {
-        if (cache_parts.o_is_bf16) {
+        if (cache_parts.o_is_16bit) {
             if (p.head_dim == 128) LS_TM_CASE(uint16_t, uint16_t, 128);
             else LS_TM_CASE(uint16_t, uint16_t, 64);
         } else {
             if (p.head_dim == 128) LS_TM_CASE(uint16_t, float, 128);
             else LS_TM_CASE(uint16_t, float, 64);
         }
+    } else if (dtype == LS_F16) {
+        if (cache_parts.o_is_16bit) {
+            if (p.head_dim == 128) LS_TM_CASE(half_t, half_t, 128);
+            else LS_TM_CASE(half_t, half_t, 64);
+        } else {
+            if (p.head_dim == 128) LS_TM_CASE(half_t, float, 128);
+            else LS_TM_CASE(half_t, float, 64);
+        }
     } else {
-        if (cache_parts.o_is_bf16) return hipErrorInvalidValue;
+        if (cache_parts.o_is_16bit) return hipErrorInvalidValue;
         if (p.head_dim == 128) LS_TM_CASE(float, float, 128);
         else LS_TM_CASE(float, float, 64);
     }

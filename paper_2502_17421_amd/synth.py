@@ -21,7 +21,7 @@ import numpy as np
 @dataclass(frozen=True)
 class Workload:
     name: str
-    dtype: str              # "bf16" | "f32"
+    dtype: str              # "bf16" | "f16" | "f32"
     batch: int
     n_q_heads: int
     n_kv_heads: int
@@ -50,6 +50,8 @@ WORKLOADS = {
     # step of beam width 16 resp. 4 (Appendix "Experiments Details") on the 8B-class GQA shape.
     "D1": Workload("D1", "bf16", 1, 32, 8, 128, 16, 32768, 32768, None, None, 1011, "cross"),
     "D2": Workload("D2", "bf16", 1, 32, 8, 128, 4, 32768, 32768, None, None, 1012, "cross"),
+    # The headline shape with IEEE half inputs, the precision of the paper's own experiments.
+    "H3": Workload("H3", "f16", 1, 32, 8, 128, 64, 32768, 32768, 8, 4, 1033),
     # The steps after the attention in a verification round (greedy acceptance + KV commit) on
     # the C3 and C5 shapes; "kind" accept.
     "A3": Workload("A3", "bf16", 1, 32, 8, 128, 64, 32768, 32768, 8, 4, 1023, "accept"),
@@ -65,6 +67,20 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     bias = ((u >> 16) & 1) + 0x7FFF
     r = ((u + bias) >> 16) << 16
     return r.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def round_to_f16(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest IEEE half (ties to even); result is float32."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def round_to(x: np.ndarray, dtype: str) -> np.ndarray:
+    """x rounded to the storage type named dtype ("bf16", "f16" or "f32"), held as float32."""
+    if dtype == "bf16":
+        return round_to_bf16(x)
+    if dtype == "f16":
+        return round_to_f16(x)
+    return np.ascontiguousarray(x, dtype=np.float32)
 
 
 def bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -171,7 +187,7 @@ class Batch:
 
 def _normal(rng, shape, dtype):
     x = rng.standard_normal(shape, dtype=np.float32)
-    return round_to_bf16(x) if dtype == "bf16" else x
+    return round_to(x, dtype)
 
 
 def make_sequence(rng: np.random.Generator, *, dtype: str, n_q_heads: int, n_kv_heads: int,
@@ -197,9 +213,8 @@ def make_sequence(rng: np.random.Generator, *, dtype: str, n_q_heads: int, n_kv_
         k_tree = np.float32(4.0) * q.reshape(n_kv_heads, g, n_tree, head_dim).mean(axis=1)
     elif variant not in ("iid", "peaked"):
         raise ValueError(variant)
-    if dtype == "bf16":
-        q = round_to_bf16(q)
-        k_tree = round_to_bf16(k_tree)
+    q = round_to(q, dtype)
+    k_tree = round_to(k_tree, dtype)
     return Sequence(q.astype(np.float32), k_cache, v_cache, k_tree.astype(np.float32), v_tree,
                     np.asarray(parents, dtype=np.int32), int(prefix_len))
 

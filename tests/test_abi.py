@@ -82,6 +82,7 @@ def good_desc(dtype=ls.LS_BF16, b=1, hq=8, hkv=2, d=128, t=16, p=1000):
 def test_validate_desc_codes():
     assert ls.ls_validate_desc(good_desc()) == ls.LS_OK
     assert ls.ls_validate_desc(good_desc(dtype=ls.LS_F32, d=64)) == ls.LS_OK
+    assert ls.ls_validate_desc(good_desc(dtype=ls.LS_F16)) == ls.LS_OK
     x = good_desc(); x.batch = 0
     assert ls.ls_validate_desc(x) == ls.LS_ERR_SHAPE
     x = good_desc(); x.n_kv_heads = 3
@@ -157,6 +158,7 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_prefix_attn_splitkv(dp, one, one, one, None, 0, ls.LS_F32, one, one, None) == ls.LS_ERR_NULL
     assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, -1, ls.LS_F32, one, one, None) == ls.LS_ERR_SHAPE
     assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, 2, 5, one, one, None) == ls.LS_ERR_DTYPE
+    assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, 2, ls.LS_F16, one, one, None) == ls.LS_ERR_DTYPE  # bf16 problem
     assert L.ls_tree_attn_masked(dp, one, one, one, None, one, one, None) == ls.LS_ERR_NULL
     assert L.ls_lse_merge(dp, 0, ls.LS_F32, one, one, one, one, None) == ls.LS_ERR_SHAPE
     assert L.ls_lse_merge(dp, 2, ls.LS_F32, one, one, None, one, None) == ls.LS_ERR_NULL

@@ -7,12 +7,17 @@ import oracle
 from paper_2502_17421_amd import binding as ls
 from paper_2502_17421_amd import synth
 
-TOL = {"bf16": 2e-2, "f32": 1e-5}          # max-abs bound on out (the stated targets)
-LSE_TOL = {"bf16": 2e-3, "f32": 1e-5}
+# max-abs bound on out: the stated targets for bf16 and f32.  f16 (11 significant bits) is not
+# named by the target; its bound follows from the arithmetic: numerators rounded toward zero
+# to 11 bits (all weights of a row shrink by up to 2^-10, on average 2^-11, which the fp32 row
+# sum does not share), split partials and the result rounded to nearest (2^-12 each):
+# <= 1e-3 of the magnitude, gated at twice that.
+TOL = {"bf16": 2e-2, "f32": 1e-5, "f16": 2e-3}
+LSE_TOL = {"bf16": 2e-3, "f32": 1e-5, "f16": 2e-4}
 
 
 def torch_dtype(name):
-    return torch.bfloat16 if name == "bf16" else torch.float32
+    return {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[name]
 
 
 def to_dev(x, dtype, device="cuda"):
@@ -116,6 +121,9 @@ def gates(got_out, got_lse, ref_out, ref_lse, dtype_name, what="", stress=False)
     if dtype_name == "bf16":
         assert max_abs <= 2e-2 * max(scale, 1e-30), info
         assert rms <= 5e-3, info
+    elif dtype_name == "f16":
+        assert max_abs <= 2e-3 * max(scale, 1e-30), info
+        assert rms <= 1e-3, info
     else:
         assert max_abs <= 1e-5 * max(1.0, scale), info
         assert rms <= 2e-6, info
