@@ -505,3 +505,31 @@ def test_full_size_peaked_c3():
     got_o = out.float().cpu().numpy()[0, rows[0, :, 0], rows[0, :, 1]][None]
     got_l = lse.cpu().numpy()[0, rows[0, :, 0], rows[0, :, 1]][None]
     say(gates(got_o, got_l, ro, rl, "bf16", "C3 full size peaked", stress=True))
+
+
+def test_whole_call_under_hip_graph_capture():
+    """The call allocates nothing and records no memset, so it can be captured; every replay
+    (with eager calls and synchronisations in between) must reproduce the eager result bit for
+    bit."""
+    batch = small("C2", 3000, "peaked")
+    db = DeviceBatch(batch)
+    db.run_full()
+    torch.cuda.synchronize()
+    ref_o, ref_l = db.out.clone(), db.lse.clone()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        db.run_full(stream=side)
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            db.run_full(stream=side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        db.out.zero_()
+        db.lse.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(db.out, ref_o) and torch.equal(db.lse, ref_l), f"replay {rep}"
+        other = DeviceBatch(small("C2", 500 + 100 * rep, "iid"))   # eager work between replays
+        other.run_full()
+        torch.cuda.synchronize()
