@@ -136,6 +136,8 @@ def main():
     ap.add_argument("--workload", default="C3",
                     help="C1..C5 (the headline metric is quoted on C3); D1, D2: cross-attention over the cache only; "
                          "A3, A5: greedy acceptance + KV commit")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="keep the cache in shuffled pages of this many rows and call ls_hybrid_tree_attn_paged")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hot", action="store_true", help="also time with one K/V copy (cache-resident)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -184,9 +186,34 @@ def main():
     n_splits = ls.ls_prefix_num_splits(db.desc)
     stream = torch.cuda.current_stream()
 
+    table = None
+    if args.page_size:
+        # the same rows scattered over shuffled pages [page, Hkv, page_size, D]; one table for all copies
+        ps = args.page_size
+        assert w.kind == "verify" and batch.max_prefix_len % ps == 0, "paged timing: whole pages, verify workloads"
+        per_seq = batch.max_prefix_len // ps
+        n_pages = w.batch * per_seq
+        perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(w.seed)).cuda()
+        table = perm.view(w.batch, per_seq).to(torch.int32).contiguous()
+
+        def to_pages(x):   # [B,Hkv,P,D] -> [B*P/ps, Hkv, ps, D] in table order
+            b, h, pl, d = x.shape
+            pages = x.view(b, h, per_seq, ps, d).permute(0, 2, 1, 3, 4).reshape(n_pages, h, ps, d)
+            out_pages = torch.empty_like(pages)
+            out_pages[perm] = pages
+            return out_pages
+
+        k_rot_c, v_rot_c = k_rot, v_rot      # the contiguous copies still serve the kernel-alone timing
+        k_rot = [to_pages(x) for x in k_rot]
+        v_rot = [to_pages(x) for x in v_rot]
+        paged_desc = ls.make_desc(db.q, k_rot[0], v_rot[0], db.k_tree, db.v_tree, db.out, batch.max_prefix_len)
+
     def call(i, r=None):
         r = i % n_rot if r is None else r
-        if w.kind == "cross":  # cached keys only: the draft model's cross-attention over the target cache
+        if table is not None:
+            ls.ls_hybrid_tree_attn_paged(paged_desc, db.q, k_rot[r], v_rot[r], table, args.page_size, db.prefix_lens,
+                                         db.k_tree, db.v_tree, db.parents, db.out, db.lse, ws, stream=stream)
+        elif w.kind == "cross":  # cached keys only: the draft model's cross-attention over the target cache
             ls.ls_cache_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.out, db.lse, ws, stream=stream)
         else:
             ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.k_tree, db.v_tree,
@@ -219,9 +246,12 @@ def main():
     o_part = torch.empty((w.batch, w.n_q_heads, n_splits, w.n_tree, w.head_dim), dtype=part_dt, device="cuda")
     l_part = torch.empty((w.batch, w.n_q_heads, n_splits, w.n_tree), dtype=torch.float32, device="cuda")
 
+    kc_alone, vc_alone = (k_rot_c, v_rot_c) if table is not None else (k_rot, v_rot)
+
     def prefix_only(i):
         r = i % n_rot
-        ls.ls_prefix_attn_splitkv(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, 0, o_part, l_part, stream=stream)
+        ls.ls_prefix_attn_splitkv(db.desc, db.q, kc_alone[r], vc_alone[r], db.prefix_lens, 0, o_part, l_part,
+                                  stream=stream)
 
     for i in range(args.warmup):
         prefix_only(i)
@@ -308,7 +338,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q heads / {w.n_kv_heads} kv heads, head_dim "
                                f"{w.head_dim}, prefix {plens}, n_tree {w.n_tree}, seed {w.seed}",
-                   "kv_layout": "[B,Hkv,P,D]", "n_splits": n_splits, "kv_rotation_copies": n_rot,
+                   "kv_layout": "[B,Hkv,P,D]" if table is None else f"shuffled pages [page,Hkv,{args.page_size},D]", "n_splits": n_splits, "kv_rotation_copies": n_rot,
                    "kv_rotation_bytes": n_rot * kv_bytes},
         "call_us": {"mean_wall": us_per_call, "event_min": float(lat.min()), "event_median": float(np.median(lat)),
                     "event_p90": float(np.percentile(lat, 90))},

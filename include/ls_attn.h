@@ -270,6 +270,41 @@ int ls_kv_commit(const ls_desc *desc, const void *k_tree, const void *v_tree,
                  void *k_cache, void *v_cache, int32_t *new_prefix_lens, int32_t *err_flag,
                  void *stream);
 
+/* ---- paged caches ---------------------------------------------------------------------- */
+
+/*
+ * ls_hybrid_tree_attn over a cache kept in fixed-size pages, the layout serving systems use
+ * when sequences grow and shrink (an extension beyond the paper, which keeps one contiguous
+ * cache per sequence): cache row r of sequence b is row r % page_size of page
+ * block_table[b * bt_stride + r / page_size].
+ *   k_pages, v_pages  DEVICE dtype; desc->kc_stride / vc_stride = {between pages, between KV
+ *                     heads inside a page, between rows inside a page}, rows 16-byte aligned
+ *   block_table       DEVICE int32[batch, bt_stride]; the entries that cover rows below
+ *                     prefix_lens[b] must be page indices of k_pages / v_pages (they are not
+ *                     checked); other entries are read but never used as addresses
+ *   page_size         a power of two >= 16;  bt_stride * page_size >= desc->max_prefix_len
+ * dtype LS_BF16 or LS_F16.  Everything else, the workspace size included, as for
+ * ls_hybrid_tree_attn.
+ */
+int ls_hybrid_tree_attn_paged(const ls_desc *desc, const void *q,
+                              const void *k_pages, const void *v_pages,
+                              const int32_t *block_table, int32_t bt_stride, int32_t page_size,
+                              const int32_t *prefix_lens,
+                              const void *k_tree, const void *v_tree, const int32_t *parents,
+                              void *out, float *lse,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * ls_kv_commit into a paged cache: row prefix_lens[b] + j of sequence b is looked up in
+ * block_table as above; the pages that receive rows must already be in the table.  page_size
+ * any power of two; any dtype.
+ */
+int ls_kv_commit_paged(const ls_desc *desc, const void *k_tree, const void *v_tree,
+                       const int32_t *accept_path, const int32_t *accept_len, const int32_t *prefix_lens,
+                       void *k_pages, void *v_pages,
+                       const int32_t *block_table, int32_t bt_stride, int32_t page_size,
+                       int32_t *new_prefix_lens, int32_t *err_flag, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -132,16 +132,21 @@ kv_commit_kernel(Problem p, int elem_bytes, const int32_t *__restrict__ accept_p
     const int chunks = p.head_dim * elem_bytes / 16;  // 16-byte pieces per row
     const uint8_t *kt = (const uint8_t *)p.k_tree + (b * p.kt_stride[0] + g * p.kt_stride[1]) * elem_bytes;
     const uint8_t *vt = (const uint8_t *)p.v_tree + (b * p.vt_stride[0] + g * p.vt_stride[1]) * elem_bytes;
-    uint8_t *kc = k_cache + (b * p.kc_stride[0] + g * p.kc_stride[1]) * elem_bytes;
-    uint8_t *vc = v_cache + (b * p.vc_stride[0] + g * p.vc_stride[1]) * elem_bytes;
+    // contiguous cache: first index = sequence; paged cache: first index = page, found per row
+    const int32_t *tab = p.block_table ? p.block_table + (size_t)b * p.bt_stride : nullptr;
+    const int page_rows_mask = (1 << p.page_shift) - 1;
     for (int e = tid; e < n * chunks; e += blockDim.x) {
         const int j = e / chunks, c = e % chunks;
         const int64_t node = path[j];
-        const int64_t row = plen + j;
+        const int row = plen + j;  // < max_prefix_len <= bt_stride * page size
+        const int64_t first = tab ? (int64_t)tab[row >> p.page_shift] : (int64_t)b;
+        const int64_t in_row = tab ? (row & page_rows_mask) : row;
         const uint4 kv = *(const uint4 *)(kt + node * p.kt_stride[2] * elem_bytes + c * 16);
         const uint4 vv = *(const uint4 *)(vt + node * p.vt_stride[2] * elem_bytes + c * 16);
-        *(uint4 *)(kc + row * p.kc_stride[2] * elem_bytes + c * 16) = kv;
-        *(uint4 *)(vc + row * p.vc_stride[2] * elem_bytes + c * 16) = vv;
+        *(uint4 *)(k_cache + (first * p.kc_stride[0] + g * p.kc_stride[1] + in_row * p.kc_stride[2]) * elem_bytes +
+                   c * 16) = kv;
+        *(uint4 *)(v_cache + (first * p.vc_stride[0] + g * p.vc_stride[1] + in_row * p.vc_stride[2]) * elem_bytes +
+                   c * 16) = vv;
     }
     if (g == 0 && tid == 0) {
         if (new_prefix_lens) new_prefix_lens[b] = plen + n;

@@ -149,6 +149,9 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
             }
         }
     }
+    // the MFMA kernel keeps the page ids of a split in registers, which bounds a split's length;
+    // the bound is applied to contiguous caches too, so that one plan serves both layouts
+    if (request <= 0 && is_16bit(d.dtype) && (max_p + s - 1) / s > kMaxSplitLen) s = (max_p + kMaxSplitLen - 1) / kMaxSplitLen;
     int64_t len = (max_p + s - 1) / s;
     len = (len + kTile - 1) / kTile * kTile;
     if (len < kTile) len = kTile;
@@ -393,6 +396,86 @@ int ls_kv_commit(const ls_desc *desc, const void *k_tree, const void *v_tree, co
     if ((int64_t)desc->batch * desc->n_kv_heads > 0x7fffffff) return LS_ERR_UNSUPPORTED;
     const Problem p = make_problem(*desc, nullptr, k_cache, v_cache, prefix_lens, k_tree, v_tree);
     return launch_kv_commit(p, desc->dtype, accept_path, accept_len, k_cache, v_cache, new_prefix_lens, err_flag,
+                            (hipStream_t)stream) == hipSuccess
+               ? LS_OK
+               : LS_ERR_HIP;
+}
+
+namespace {
+
+// page_size: a power of two >= 16; the table must cover max_prefix_len rows
+int check_paging(const ls_desc *desc, const int32_t *block_table, int32_t bt_stride, int32_t page_size)
+{
+    if (!block_table) return LS_ERR_NULL;
+    if (page_size <= 0 || bt_stride <= 0) return LS_ERR_SHAPE;
+    if (page_size < 16 || (page_size & (page_size - 1)) != 0) return LS_ERR_UNSUPPORTED;
+    if ((int64_t)bt_stride * page_size < desc->max_prefix_len) return LS_ERR_SHAPE;
+    if (!is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;  // the float kernel reads contiguous caches only
+    return LS_OK;
+}
+
+int page_shift_of(int32_t page_size)
+{
+    int s = 0;
+    while ((1 << s) < page_size) ++s;
+    return s;
+}
+
+}  // namespace
+
+int ls_hybrid_tree_attn_paged(const ls_desc *desc, const void *q, const void *k_pages, const void *v_pages,
+                              const int32_t *block_table, int32_t bt_stride, int32_t page_size,
+                              const int32_t *prefix_lens, const void *k_tree, const void *v_tree,
+                              const int32_t *parents, void *out, float *lse, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    int rc = validate(desc);
+    if (rc) return rc;
+    if (!q || !prefix_lens || !k_tree || !v_tree || !parents || !out || !lse) return LS_ERR_NULL;
+    if (desc->max_prefix_len > 0 && (!k_pages || !v_pages)) return LS_ERR_NULL;
+    if ((rc = check_paging(desc, block_table, bt_stride, page_size))) return rc;
+    if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(k_tree) || !aligned16(v_tree) ||
+        !aligned16(out))
+        return LS_ERR_STRIDE;
+    const SplitPlan plan = plan_splits(*desc, 0);
+    const Workspace w = layout(*desc, plan);
+    if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < w.total) return LS_ERR_WORKSPACE;
+    if (plan.split_len > kMaxSplitLen) return LS_ERR_UNSUPPORTED;
+    char *base = (char *)workspace;
+    uint64_t *mask = (uint64_t *)(base + w.off_mask);
+    int32_t *err = (int32_t *)(base + w.off_err);
+    Problem p = make_problem(*desc, q, k_pages, v_pages, prefix_lens, k_tree, v_tree);
+    p.block_table = block_table;
+    p.bt_stride = bt_stride;
+    p.page_shift = page_shift_of(page_size);
+    if (!prefix_mfma_supports(p, desc->dtype)) return LS_ERR_UNSUPPORTED;
+    const Partials parts{base + w.off_o, (float *)(base + w.off_lse), w.n_parts, 0, 1};
+    hipStream_t s = (hipStream_t)stream;
+    if (launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{parents, mask, err}, s) != hipSuccess) return LS_ERR_HIP;
+    if (launch_tree_merge(p, desc->dtype, mask, parts, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)
+        return LS_ERR_HIP;
+    return LS_OK;
+}
+
+int ls_kv_commit_paged(const ls_desc *desc, const void *k_tree, const void *v_tree, const int32_t *accept_path,
+                       const int32_t *accept_len, const int32_t *prefix_lens, void *k_pages, void *v_pages,
+                       const int32_t *block_table, int32_t bt_stride, int32_t page_size, int32_t *new_prefix_lens,
+                       int32_t *err_flag, void *stream)
+{
+    int rc = validate(desc);
+    if (rc) return rc;
+    if (!k_tree || !v_tree || !accept_path || !accept_len || !prefix_lens || !k_pages || !v_pages) return LS_ERR_NULL;
+    if (new_prefix_lens == prefix_lens) return LS_ERR_NULL;
+    if (!block_table) return LS_ERR_NULL;
+    if (page_size <= 0 || bt_stride <= 0) return LS_ERR_SHAPE;
+    if ((page_size & (page_size - 1)) != 0) return LS_ERR_UNSUPPORTED;
+    if ((int64_t)bt_stride * page_size < desc->max_prefix_len) return LS_ERR_SHAPE;
+    if (!aligned16(k_tree) || !aligned16(v_tree) || !aligned16(k_pages) || !aligned16(v_pages)) return LS_ERR_STRIDE;
+    Problem p = make_problem(*desc, nullptr, k_pages, v_pages, prefix_lens, k_tree, v_tree);
+    p.block_table = block_table;
+    p.bt_stride = bt_stride;
+    p.page_shift = page_shift_of(page_size);
+    return launch_kv_commit(p, desc->dtype, accept_path, accept_len, k_pages, v_pages, new_prefix_lens, err_flag,
                             (hipStream_t)stream) == hipSuccess
                ? LS_OK
                : LS_ERR_HIP;

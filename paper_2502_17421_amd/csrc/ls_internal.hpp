@@ -12,6 +12,8 @@ namespace ls {
 constexpr int kWave = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kMaxSplitPages = 512;  // pages one key split of the MFMA kernel may touch (page ids sit in 8 registers)
+constexpr int kMaxSplitLen = 8192;    // cache rows per split on the MFMA path: 512 pages of the smallest page size, 16
 
 // Everything a kernel needs to find its operands; passed by value.
 struct Problem {
@@ -21,6 +23,11 @@ struct Problem {
     const void *k_tree;
     const void *v_tree;
     const int32_t *prefix_lens;
+    // Paged cache (block_table != nullptr): cache row r of sequence b lives in page
+    // block_table[b * bt_stride + (r >> page_shift)] at row r & (page_size - 1); kc_stride /
+    // vc_stride then mean {between pages, between KV heads inside a page, between rows}.
+    const int32_t *block_table;
+    int32_t bt_stride, page_shift;
     int32_t batch, n_q_heads, n_kv_heads, group, head_dim, n_tree, max_prefix_len;
     float scale_log2;  // softmax scale times log2(e): logits are kept in base 2 inside kernels
     int64_t q_stride[3], kc_stride[3], vc_stride[3], kt_stride[3], vt_stride[3];

@@ -242,7 +242,61 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
         k_voff[j] = (uint32_t)(row * k_row_bytes) + (ld_pos ^ (row & (CH - 1))) * 16;
         v_voff[j] = (uint32_t)(row * v_row_bytes) + (ld_pos ^ (vswz(row) & (CH - 1))) * 16;
     }
+    // Paged cache: the ids of the pages this split touches, page (first_page + 64 j + l) in lane
+    // l of register j; a tile request then finds its pages with register reads only.
+    const bool paged = p.block_table != nullptr;
+    const int page_rows_mask = (1 << p.page_shift) - 1;
+    const int first_page = k_lo >> p.page_shift;
+    uint32_t page_tab[kMaxSplitPages / 64] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (paged) {
+        const int32_t *tab = p.block_table + (size_t)b * p.bt_stride;
+#pragma unroll
+        for (int j = 0; j < kMaxSplitPages / 64; ++j) {
+            const int idx = first_page + 64 * j + lane;
+            page_tab[j] = idx < p.bt_stride ? (uint32_t)tab[idx] : 0u;
+        }
+    }
+    auto page_of = [&](int row) -> int64_t {  // row: wave-uniform cache row of this sequence
+        const int pidx = (row >> p.page_shift) - first_page;
+        const int sel = pidx & 63;
+        uint32_t id = __builtin_amdgcn_readlane(page_tab[0], sel);
+#pragma unroll
+        for (int j = 1; j < kMaxSplitPages / 64; ++j)
+            if ((pidx >> 6) == j) id = __builtin_amdgcn_readlane(page_tab[j], sel);
+        return (int64_t)id;
+    };
+    // One load instruction covers ROWS_PER_LOAD consecutive rows, which never straddle a page
+    // (page sizes are powers of two >= 16): its base is that of its own page.
+    auto issue_tile_paged = [&](int k0, int stage) {
+        const uint32_t ks_off = __builtin_amdgcn_readfirstlane(smem_off + stage * STAGEB);
+        const int last = k_hi - 1 - k0;  // last valid row of the tile (>= TK - 1 for whole tiles)
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const int row0 = (wave * LOADS + j) * ROWS_PER_LOAD;  // wave-uniform
+            // rows past the end of the split repeat its last row, fetched through that row's own group
+            const int last_group = last & ~(ROWS_PER_LOAD - 1);
+            const int src0 = row0 < last_group ? row0 : last_group;
+            const int row = row0 + ld_row;
+            int src = src0 + ld_row;
+            src = src < last ? src : last;
+            const int abs0 = k0 + src0;
+            const int64_t page = page_of(abs0);
+            const int in_page = abs0 & page_rows_mask;
+            const uint8_t *kb = uniform_ptr((const uint8_t *)p.k_cache +
+                                            (page * p.kc_stride[0] + g * p.kc_stride[1] + in_page * p.kc_stride[2]) * 2);
+            const uint8_t *vb = uniform_ptr((const uint8_t *)p.v_cache +
+                                            (page * p.vc_stride[0] + g * p.vc_stride[1] + in_page * p.vc_stride[2]) * 2);
+            const uint32_t ko = (uint32_t)((src - src0) * k_row_bytes) + (ld_pos ^ (row & (CH - 1))) * 16;
+            const uint32_t vo = (uint32_t)((src - src0) * v_row_bytes) + (ld_pos ^ (vswz(row) & (CH - 1))) * 16;
+            copy_to_lds(kb, ko, ks_off + row0 * ROWB);
+            copy_to_lds(vb, vo, ks_off + TILEB + row0 * ROWB);
+        }
+    };
     auto issue_tile = [&](int k0, int stage) {
+        if (paged) {
+            issue_tile_paged(k0, stage);
+            return;
+        }
         const uint32_t ks_off = __builtin_amdgcn_readfirstlane(smem_off + stage * STAGEB);
         const uint8_t *kt_base = uniform_ptr(kbase + k0 * k_row_bytes);
         const uint8_t *vt_base = uniform_ptr(vbase + k0 * v_row_bytes);
