@@ -169,6 +169,14 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_kv_commit(dp, one, one, one, one, one, None, one, None, None, None) == ls.LS_ERR_NULL
     assert L.ls_kv_commit(dp, one, one, one, one, one, one, one, one, None, None) == ls.LS_ERR_NULL   # aliasing lengths
     assert L.ls_kv_commit(dp, one, odd, one, one, one, one, one, None, None, None) == ls.LS_ERR_STRIDE
+    big = 1 << 40
+    assert L.ls_hybrid_tree_attn_paged(dp, one, one, one, None, 64, 16, one, one, one, one, one, one, one, big, None) == ls.LS_ERR_NULL
+    assert L.ls_hybrid_tree_attn_paged(dp, one, one, one, one, 64, 24, one, one, one, one, one, one, one, big, None) == ls.LS_ERR_UNSUPPORTED
+    assert L.ls_hybrid_tree_attn_paged(dp, one, one, one, one, 2, 16, one, one, one, one, one, one, one, big, None) == ls.LS_ERR_SHAPE
+    f32 = good_desc(dtype=ls.LS_F32, d=64)
+    assert L.ls_hybrid_tree_attn_paged(ctypes.byref(f32), one, one, one, one, 64, 16, one, one, one, one, one, one, one, big, None) == ls.LS_ERR_UNSUPPORTED
+    assert L.ls_kv_commit_paged(dp, one, one, one, one, one, one, one, None, 64, 16, None, None, None) == ls.LS_ERR_NULL
+    assert L.ls_kv_commit_paged(dp, one, one, one, one, one, one, one, one, 64, 24, None, None, None) == ls.LS_ERR_UNSUPPORTED
 
 
 def test_binding_raises_when_library_is_missing(tmp_path, monkeypatch):
