@@ -50,6 +50,9 @@ WORKLOADS = {
     # step of beam width 16 resp. 4 (Appendix "Experiments Details") on the 8B-class GQA shape.
     "D1": Workload("D1", "bf16", 1, 32, 8, 128, 16, 32768, 32768, None, None, 1011, "cross"),
     "D2": Workload("D2", "bf16", 1, 32, 8, 128, 4, 32768, 32768, None, None, 1012, "cross"),
+    # The draft model's own self-attention (Section 3.1): a sliding window of 512 cached rows plus
+    # the tokens drafted so far (68 nodes after the five beam steps of the appendix).
+    "W1": Workload("W1", "bf16", 1, 32, 8, 128, 68, 512, 512, 5, 16, 1041),
     # The headline shape with IEEE half inputs, the precision of the paper's own experiments.
     "H3": Workload("H3", "f16", 1, 32, 8, 128, 64, 32768, 32768, 8, 4, 1033),
     # The steps after the attention in a verification round (greedy acceptance + KV commit) on

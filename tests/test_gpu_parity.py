@@ -533,3 +533,14 @@ def test_whole_call_under_hip_graph_capture():
         other = DeviceBatch(small("C2", 500 + 100 * rep, "iid"))   # eager work between replays
         other.run_full()
         torch.cuda.synchronize()
+
+
+def test_draft_window_self_attention_shape():
+    """The draft model's sliding-window self-attention (Section 3.1): at most 512 cached rows
+    plus the drafted tree; the same call at a short prefix."""
+    batch = synth.make_batch(synth.WORKLOADS["W1"], "peaked")
+    db = DeviceBatch(batch)
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, "bf16", "W1 window 512 + 68-node tree", stress=True))
