@@ -327,11 +327,11 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache,
 
     // (b) cached keys -> parts [0, n_splits), stored in the problem's dtype; on the MFMA path
     // the same launch carries the workgroups of (a), the tree mask
-    const Partials cache_out{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype)};
+    const Partials cache_out{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype), 1};
     if (prefix_mfma_supports(p, desc->dtype)) {
         if (launch_prefix_mfma(p, desc->dtype, plan, cache_out, MaskJob{parents, mask, err}, s) != hipSuccess) return LS_ERR_HIP;
     } else {
-        const Partials f32_out{o_parts, lse_parts, w.n_parts, 0, 0};
+        const Partials f32_out{o_parts, lse_parts, w.n_parts, 0, 0, 1};
         if (is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;  // 16-bit row strides beyond the MFMA kernel's range
         if (launch_prefix_valu(p, desc->dtype, plan, f32_out, s) != hipSuccess) return LS_ERR_HIP;
         if (launch_tree_mask(parents, desc->batch, desc->n_tree, mask, err, s) != hipSuccess) return LS_ERR_HIP;
@@ -361,7 +361,7 @@ int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const
     const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, nullptr, nullptr);
     const bool mfma = prefix_mfma_supports(p, desc->dtype);
     if (!mfma && is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;
-    const Partials parts{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype)};
+    const Partials parts{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype), 1};
     const hipError_t e = mfma ? launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s)
                               : launch_prefix_valu(p, desc->dtype, plan, parts, s);
     if (e != hipSuccess) return LS_ERR_HIP;
@@ -449,7 +449,7 @@ int ls_hybrid_tree_attn_paged(const ls_desc *desc, const void *q, const void *k_
     p.bt_stride = bt_stride;
     p.page_shift = page_shift_of(page_size);
     if (!prefix_mfma_supports(p, desc->dtype)) return LS_ERR_UNSUPPORTED;
-    const Partials parts{base + w.off_o, (float *)(base + w.off_lse), w.n_parts, 0, 1};
+    const Partials parts{base + w.off_o, (float *)(base + w.off_lse), w.n_parts, 0, 1, 1};
     hipStream_t s = (hipStream_t)stream;
     if (launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{parents, mask, err}, s) != hipSuccess) return LS_ERR_HIP;
     if (launch_tree_merge(p, desc->dtype, mask, parts, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)

@@ -42,6 +42,16 @@ struct Partials {
     int32_t parts_stride;
     int32_t part_base;
     int32_t o_is_16bit;
+    // 0: [.., part, tree row, ..] (the layout of the public subsystem entry points);
+    // 1: [.., tree row, part, ..]: the parts of one query row lie side by side, which is what
+    //    the kernel that merges them reads (the whole-path calls use this inside the workspace)
+    int32_t row_major;
+    // index of (b, h, part, tree row i) into lse, and times head_dim into o
+    __host__ __device__ size_t row(size_t bh, int part, int n_tree, int i) const
+    {
+        return row_major ? (bh * n_tree + i) * parts_stride + part_base + part
+                         : (bh * parts_stride + part_base + part) * n_tree + i;
+    }
 };
 
 // Work appended to the cached-key launch so that the whole call needs one launch less:

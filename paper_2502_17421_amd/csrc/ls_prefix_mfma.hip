@@ -209,8 +209,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     const bool q_ok = m_row < rows_kv;
     const int hq = g * p.group + (q_ok ? m_row / p.n_tree : 0);
     const int ti = q_ok ? m_row % p.n_tree : 0;
-    const size_t part_row =
-        (((size_t)b * p.n_q_heads + hq) * out.parts_stride + out.part_base + split) * p.n_tree + ti;
+    const size_t part_row = out.row((size_t)b * p.n_q_heads + hq, split, p.n_tree, ti);
 
     if (k_lo >= k_hi) {  // empty split: weight zero in the merge
         if (lh == 0 && q_ok) out.lse[part_row] = -INFINITY;

@@ -181,8 +181,7 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
     }
 
     if (!row_ok) return;
-    const size_t prow =
-        (((size_t)b * p.n_q_heads + hq) * out.parts_stride + out.part_base + split) * p.n_tree + ti;
+    const size_t prow = out.row((size_t)b * p.n_q_heads + hq, split, p.n_tree, ti);
     if (l_run > 0.f) {
         const float inv = 1.f / l_run;
         float *orow = (float *)out.o + prow * D;

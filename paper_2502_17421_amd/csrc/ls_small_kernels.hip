@@ -78,7 +78,7 @@ tree_attn_kernel(Problem p, const uint64_t *__restrict__ mask, Partials out)
             m_run = m_new;
         }
     }
-    const size_t prow = (((size_t)b * p.n_q_heads + h) * out.parts_stride + out.part_base) * p.n_tree + i;
+    const size_t prow = out.row((size_t)b * p.n_q_heads + h, 0, p.n_tree, i);
     float *orow = (float *)out.o + prow * D;
     const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
 #pragma unroll
@@ -323,10 +323,11 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
     const int g = h / p.group;
     const int words = (p.n_tree + 63) >> 6;
 
-    const size_t prow0 = (((size_t)b * p.n_q_heads + h) * parts.parts_stride + parts.part_base) * p.n_tree + i;
+    const size_t prow0 = parts.row((size_t)b * p.n_q_heads + h, 0, p.n_tree, i);
     const float *lp = parts.lse + prow0;
     const PT *op = (const PT *)parts.o + prow0 * D + lane * EPL;
-    const size_t part_step = (size_t)p.n_tree * D;  // elements between consecutive parts of one row
+    const size_t lse_step = parts.row_major ? 1 : (size_t)p.n_tree;  // between consecutive parts of one row
+    const size_t part_step = lse_step * D;
 
     // Order of requests (loads return in the order they were issued): the query row and the
     // mask word first, a short round trip; then the row's first visible tree keys; then the
@@ -389,7 +390,7 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
         request_keys(bits0, 0);
     }
     // the first 64 part LSEs (one per lane) and the first CHUNK split rows
-    const float l_first = lane < n_cache ? lp[(size_t)lane * p.n_tree] : -INFINITY;
+    const float l_first = lane < n_cache ? lp[(size_t)lane * lse_step] : -INFINITY;
     typename RP::type raw[CHUNK];
 #pragma unroll
     for (int k = 0; k < CHUNK; ++k) {
@@ -401,7 +402,7 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
     float top_c = wave_max(l_first);
     for (int s0 = kWave; s0 < n_cache; s0 += kWave) {
         const int s = s0 + lane;
-        const float l = s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY;
+        const float l = s < n_cache ? lp[(size_t)s * lse_step] : -INFINITY;
         top_c = fmaxf(top_c, wave_max(l));
     }
     float o[EPL];
@@ -411,7 +412,7 @@ tree_merge_kernel(Problem p, const uint64_t *__restrict__ mask, Partials parts, 
     if (top_c != -INFINITY) {
         for (int s0 = 0; s0 < n_cache; s0 += kWave) {
             const int s = s0 + lane;
-            const float l = s0 == 0 ? l_first : (s < n_cache ? lp[(size_t)s * p.n_tree] : -INFINITY);
+            const float l = s0 == 0 ? l_first : (s < n_cache ? lp[(size_t)s * lse_step] : -INFINITY);
             const float w = l == -INFINITY ? 0.f : exp2f((l - top_c) * kLog2e);
             w_lane += w;
             const int cnt = n_cache - s0 < kWave ? n_cache - s0 : kWave;
