@@ -269,7 +269,7 @@ int ls_prefix_attn_splitkv(const ls_desc *desc, const void *q, const void *k_cac
         e = launch_prefix_mfma(p, desc->dtype, plan, out, MaskJob{nullptr, nullptr, nullptr}, (hipStream_t)stream);
     } else {
         if (part_dtype != LS_F32) return LS_ERR_UNSUPPORTED;
-        e = launch_prefix_valu(p, desc->dtype, plan, out, (hipStream_t)stream);
+        e = launch_prefix_valu(p, desc->dtype, plan, out, MaskJob{nullptr, nullptr, nullptr}, (hipStream_t)stream);
     }
     return e == hipSuccess ? LS_OK : LS_ERR_HIP;
 }
@@ -333,8 +333,12 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache,
     } else {
         const Partials f32_out{o_parts, lse_parts, w.n_parts, 0, 0, 1};
         if (is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;  // 16-bit row strides beyond the MFMA kernel's range
-        if (launch_prefix_valu(p, desc->dtype, plan, f32_out, s) != hipSuccess) return LS_ERR_HIP;
-        if (launch_tree_mask(parents, desc->batch, desc->n_tree, mask, err, s) != hipSuccess) return LS_ERR_HIP;
+        // the mask rides on the same launch when its grid slice has a workgroup per sequence
+        const int n_qblocks = (p.group * p.n_tree + 31) / 32;
+        const bool ride = (int64_t)plan.n_splits * n_qblocks >= desc->batch;
+        if (launch_prefix_valu(p, desc->dtype, plan, f32_out, ride ? MaskJob{parents, mask, err} : MaskJob{nullptr, nullptr, nullptr}, s) != hipSuccess)
+            return LS_ERR_HIP;
+        if (!ride && launch_tree_mask(parents, desc->batch, desc->n_tree, mask, err, s) != hipSuccess) return LS_ERR_HIP;
     }
     // (c) tree keys and (d) merge, one wavefront per query row
     if (launch_tree_merge(p, desc->dtype, mask, cache_out, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)
@@ -363,7 +367,7 @@ int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const
     if (!mfma && is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;
     const Partials parts{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype), 1};
     const hipError_t e = mfma ? launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s)
-                              : launch_prefix_valu(p, desc->dtype, plan, parts, s);
+                              : launch_prefix_valu(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s);
     if (e != hipSuccess) return LS_ERR_HIP;
     // the tail kernel without a mask: merge of the split partials only
     if (launch_tree_merge(p, desc->dtype, nullptr, parts, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)

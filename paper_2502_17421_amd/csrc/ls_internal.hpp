@@ -148,7 +148,7 @@ hipError_t launch_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tre
 hipError_t launch_tree_attn(const Problem &p, int dtype, const uint64_t *mask, const Partials &out,
                             hipStream_t stream);
 hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
-                              hipStream_t stream);
+                              const MaskJob &mask_job, hipStream_t stream);
 hipError_t launch_prefix_mfma(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
                               const MaskJob &mask_job, hipStream_t stream);
 bool prefix_mfma_supports(const Problem &p, int dtype);

@@ -32,7 +32,7 @@ __device__ __forceinline__ float4 load4(const half_t *p)
 
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
-prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
+prefix_valu_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job)
 {
     constexpr int KP = D + 4;  // padded row, still 16-byte aligned: the 8 rows a wave reads together hit distinct banks
     __shared__ __attribute__((aligned(16))) float q_s[TQ][KP];
@@ -42,6 +42,17 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
 
     const int tid = threadIdx.x;
     const int r = tid >> 3, c = tid & 7;
+    // One extra z-slice of the grid (present only in the whole-path launch) builds the tree masks,
+    // one workgroup per sequence, so that the call needs one launch less.
+    if ((int)blockIdx.z == p.batch * p.n_kv_heads) {
+        const int mb = blockIdx.y * gridDim.x + blockIdx.x;
+        if (mb >= p.batch) return;
+        const int words = (p.n_tree + 63) >> 6;
+        build_tree_mask_rows(mask_job.parents + (size_t)mb * p.n_tree, p.n_tree,
+                             mask_job.mask + (size_t)mb * p.n_tree * words,
+                             mask_job.err_flag ? mask_job.err_flag + mb : nullptr, tid);
+        return;
+    }
     const int split = blockIdx.x;
     const int qblock = blockIdx.y;
     const int b = blockIdx.z / p.n_kv_heads;
@@ -196,11 +207,17 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out)
 }
 
 hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
-                              hipStream_t stream)
+                              const MaskJob &mask_job, hipStream_t stream)
 {
     const int rows_kv = p.group * p.n_tree;
-    const dim3 block(256), grid(plan.n_splits, (rows_kv + TQ - 1) / TQ, p.batch * p.n_kv_heads);
-#define LS_PV_CASE(T, DD) hipLaunchKernelGGL((prefix_valu_kernel<T, DD>), grid, block, 0, stream, p, plan, out)
+    const int n_qblocks = (rows_kv + TQ - 1) / TQ;
+    const bool with_mask = mask_job.parents != nullptr;
+    // the mask slice offers n_splits * n_qblocks workgroups: enough for the batch?
+    if (with_mask && (int64_t)plan.n_splits * n_qblocks < p.batch) return hipErrorInvalidValue;
+    const dim3 block(256), grid(plan.n_splits, n_qblocks, p.batch * p.n_kv_heads + (with_mask ? 1 : 0));
+    static_assert(256 >= LS_MAX_TREE, "the mask workgroups need one thread per tree token");
+#define LS_PV_CASE(T, DD) \
+    hipLaunchKernelGGL((prefix_valu_kernel<T, DD>), grid, block, 0, stream, p, plan, out, mask_job)
     if (dtype == LS_BF16 && p.head_dim == 128) LS_PV_CASE(uint16_t, 128);
     else if (dtype == LS_BF16 && p.head_dim == 64) LS_PV_CASE(uint16_t, 64);
     else if (dtype == LS_F16 && p.head_dim == 128) LS_PV_CASE(half_t, 128);
