@@ -294,6 +294,13 @@ int ls_hybrid_tree_attn_paged(const ls_desc *desc, const void *q,
                               void *out, float *lse,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* ls_cache_attn over a paged cache; paging arguments as for ls_hybrid_tree_attn_paged. */
+int ls_cache_attn_paged(const ls_desc *desc, const void *q,
+                        const void *k_pages, const void *v_pages,
+                        const int32_t *block_table, int32_t bt_stride, int32_t page_size,
+                        const int32_t *prefix_lens, void *out, float *lse,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
 /*
  * ls_kv_commit into a paged cache: row prefix_lens[b] + j of sequence b is looked up in
  * block_table as above; the pages that receive rows must already be in the table.  page_size

@@ -74,11 +74,13 @@ def lib() -> ctypes.CDLL:
     L.ls_kv_commit.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
     L.ls_hybrid_tree_attn_paged.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                             _vp]
+    L.ls_cache_attn_paged.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_kv_commit_paged.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
     for name in ("ls_validate_desc", "ls_validate_parents_host", "ls_prefix_num_splits", "ls_prefix_split_len",
                  "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_cache_attn", "ls_build_tree_mask",
                  "ls_prefix_attn_splitkv", "ls_tree_attn_masked", "ls_lse_merge", "ls_tree_accept_greedy",
-                 "ls_kv_commit", "ls_hybrid_tree_attn_paged", "ls_kv_commit_paged"):
+                 "ls_kv_commit", "ls_hybrid_tree_attn_paged", "ls_cache_attn_paged",
+                 "ls_kv_commit_paged"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -288,4 +290,14 @@ def ls_kv_commit_paged(desc, k_tree, v_tree, accept_path, accept_len, prefix_len
                                   _stream(stream))
     if check:
         _check(st, "ls_kv_commit_paged")
+    return int(st)
+
+
+def ls_cache_attn_paged(desc, q, k_pages, v_pages, block_table, page_size, prefix_lens, out, lse, workspace,
+                        stream=None, check: bool = True) -> int:
+    st = lib().ls_cache_attn_paged(ctypes.byref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                   block_table.shape[1], int(page_size), _ptr(prefix_lens), _ptr(out), _ptr(lse),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if check:
+        _check(st, "ls_cache_attn_paged")
     return int(st)

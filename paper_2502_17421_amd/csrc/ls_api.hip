@@ -461,6 +461,35 @@ int ls_hybrid_tree_attn_paged(const ls_desc *desc, const void *q, const void *k_
     return LS_OK;
 }
 
+int ls_cache_attn_paged(const ls_desc *desc, const void *q, const void *k_pages, const void *v_pages,
+                        const int32_t *block_table, int32_t bt_stride, int32_t page_size, const int32_t *prefix_lens,
+                        void *out, float *lse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = validate(desc);
+    if (rc) return rc;
+    if (!q || !prefix_lens || !out || !lse) return LS_ERR_NULL;
+    if (desc->max_prefix_len > 0 && (!k_pages || !v_pages)) return LS_ERR_NULL;
+    if ((rc = check_paging(desc, block_table, bt_stride, page_size))) return rc;
+    if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out)) return LS_ERR_STRIDE;
+    const SplitPlan plan = plan_splits(*desc, 0);
+    const Workspace w = layout(*desc, plan);
+    if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < w.total) return LS_ERR_WORKSPACE;
+    if (plan.split_len > kMaxSplitLen) return LS_ERR_UNSUPPORTED;
+    char *base = (char *)workspace;
+    Problem p = make_problem(*desc, q, k_pages, v_pages, prefix_lens, nullptr, nullptr);
+    p.block_table = block_table;
+    p.bt_stride = bt_stride;
+    p.page_shift = page_shift_of(page_size);
+    if (!prefix_mfma_supports(p, desc->dtype)) return LS_ERR_UNSUPPORTED;
+    const Partials parts{base + w.off_o, (float *)(base + w.off_lse), w.n_parts, 0, 1, 1};
+    hipStream_t s = (hipStream_t)stream;
+    if (launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s) != hipSuccess)
+        return LS_ERR_HIP;
+    if (launch_tree_merge(p, desc->dtype, nullptr, parts, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)
+        return LS_ERR_HIP;
+    return LS_OK;
+}
+
 int ls_kv_commit_paged(const ls_desc *desc, const void *k_tree, const void *v_tree, const int32_t *accept_path,
                        const int32_t *accept_len, const int32_t *prefix_lens, void *k_pages, void *v_pages,
                        const int32_t *block_table, int32_t bt_stride, int32_t page_size, int32_t *new_prefix_lens,

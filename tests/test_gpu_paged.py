@@ -126,6 +126,17 @@ def test_paged_equals_contiguous_bit_for_bit():
     assert np.array_equal(out_p, out_c.float().cpu().numpy()) and np.array_equal(lse_p, lse_c.cpu().numpy())
 
 
+def test_cache_only_paged():
+    batch = batch_of("bf16", 32, 8, 128, 16, [3000, 70], "peaked", 9990)
+    pb = PagedBatch(batch, 16, np.random.default_rng(6))
+    ls.ls_cache_attn_paged(pb.desc, pb.q, pb.k_pages, pb.v_pages, pb.table, 16, pb.prefix_lens, pb.out, pb.lse, pb.ws)
+    torch.cuda.synchronize()
+    for b, sq in enumerate(batch.seqs):
+        ro, rl = oracle.attn_all(sq.q, sq.k_cache, sq.v_cache, sq.k_tree, sq.v_tree, sq.parents, use_tree=False)
+        say(gates(pb.out[b].float().cpu().numpy(), pb.lse[b].cpu().numpy(), ro, rl, "bf16",
+                  f"paged cache only P={sq.prefix_len}", stress=True))
+
+
 def test_paged_argument_errors():
     batch = batch_of("bf16", 8, 2, 128, 8, [300], "iid", 9950)
     pb = PagedBatch(batch, 64, np.random.default_rng(5))
