@@ -1,4 +1,5 @@
-// Split-KV attention over the cached keys on the bf16 matrix cores (gfx950 MFMA).
+// Split-KV attention over the cached keys on the 16-bit matrix cores (gfx950 MFMA; bf16 or
+// IEEE half inputs, selected by the template flag F16, fp32 accumulation either way).
 // Step (b) of the path: per key split, o_cache and LSE_cache of the aggregation appendix.
 //
 // Work decomposition.  All G*T query rows that share a KV head (G query heads x T tree
@@ -19,6 +20,10 @@
 // all workgroups start together, and without this their addresses would differ only by
 // multiples of the split size and crowd a few memory channels.
 //
+// Paged caches: a load instruction covers 4 or 8 consecutive rows, which a page of 16 rows
+// or more never splits, so each instruction takes the base of its own page; the page ids of
+// the split sit in registers (one lane per page) and are picked with v_readlane.
+//
 // The partial outputs leave through LDS (free by then) as whole 16-byte-per-lane rows with
 // streaming stores; stored straight from the accumulator layout every store would touch 32
 // rows with 16 bytes each.
@@ -27,7 +32,7 @@
 // M axis, queries along N).  With the 32x32 accumulator layout a lane then holds, for ONE
 // query (column = lane % 32), 4-key runs of the tile: exactly the per-lane contraction
 // slices that the B operand of the next product O^T = V^T P^T needs.  So the softmax
-// numerators go from accumulator registers to the second MFMA with a bf16 pack and no
+// numerators go from accumulator registers to the second MFMA with a 16-bit pack and no
 // cross-lane traffic, and the per-query max / sum are a register reduction plus one
 // exchange between the two 32-lane halves.  V^T (the A operand of the second product)
 // is read from the row-major V tile with the LDS transpose read ds_read_b64_tr_b16.
@@ -36,11 +41,12 @@
 // the sum l of exp2((s - m) * c) over the keys seen, c = scale * log2(e).  m need not be
 // the running maximum: any m gives the same O = sum p v / l and LSE = m*c + log2 l as long
 // as nothing overflows.  After the first 32 keys have set m, the common path therefore
-// skips the max search and only checks that the row sums stay below 2^40; a wave that sees
+// skips the max search and only checks that the row sums stay below 2^40 (2^15 for halves,
+// whose largest finite value is 65504); a wave that sees
 // a larger sum (scores far above everything before) redoes that step on the general path,
 // which raises m and rescales O and l.
 //
-// MFMA layouts used (v_mfma_f32_32x32x16_bf16, A is 32xK, B is Kx32, K = 16):
+// MFMA layouts used (v_mfma_f32_32x32x16_bf16 / _f16, A is 32xK, B is Kx32, K = 16):
 //   A: lane l holds row l % 32, contraction indices 8*(l/32) .. 8*(l/32)+7
 //   B: lane l holds column l % 32, same contraction indices
 //   C/D: lane l, register r holds row 8*(r/4) + 4*(l/32) + r%4, column l % 32
