@@ -312,6 +312,20 @@ int ls_kv_commit_paged(const ls_desc *desc, const void *k_tree, const void *v_tr
                        const int32_t *block_table, int32_t bt_stride, int32_t page_size,
                        int32_t *new_prefix_lens, int32_t *err_flag, void *stream);
 
+/* ---- measurement helpers (nothing of the method) ---------------------------------------- */
+
+/*
+ * What the card reaches in practice, for the benchmark to quote beside the kernels' figures
+ * (Section 4 of the paper measures wall-clock speed; these give the ceilings on this GPU).
+ * ls_probe_stream_read reads `bytes` (>= 16, 16-byte aligned DEVICE memory) once with every
+ * compute unit and writes nothing but, possibly, 16 bytes at `sink` (DEVICE).
+ * ls_probe_mfma_loop issues `iters` rounds of independent bf16 32x32x16 MFMAs from two waves
+ * per SIMD on every compute unit; *flops_out (HOST, may be NULL) receives the flop count.
+ * Both enqueue one kernel on `stream`; time them with events.
+ */
+int ls_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+int ls_probe_mfma_loop(int32_t iters, void *sink, int64_t *flops_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif
