@@ -486,6 +486,17 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     wait_tile(0);
     __syncthreads();
     if (PD < n_tiles) issue_tile(tile_k0(PD), PD % NS);
+    // A wave whose 32 rows all lie past the last query row of the KV head (the last query block
+    // of a head whose row count is not a multiple of the block) only keeps feeding the ring:
+    // its share of every tile, and every barrier of the loop below.
+    if ((qblock * NW + wave) * 32 >= rows_kv) {
+        for (int t = 0; t + 1 < n_tiles; ++t) {
+            wait_tile(t + 1);
+            __syncthreads();
+            if (t + 1 + PD < n_tiles) issue_tile(tile_k0(t + 1 + PD), (t + 1 + PD) % NS);
+        }
+        return;
+    }
     fetch_k(smem, 0, k_frag);
     s_cur = score(k_frag);
     mask_tail(s_cur, tile_k0(0));
