@@ -125,9 +125,9 @@ int ls_workspace_bytes(const ls_desc *desc, size_t *bytes_out);
 
 /*
  * The whole path (Section 3.3): tree mask from `parents`, split-KV attention over the
- * cache, masked attention over the tree tokens, log-sum-exp merge into out / lse.  For
- * bf16 and f16 problems it runs as two launches: the cached-key kernel (whose last workgroups also
- * build the mask), then one kernel that does the tree attention and the merge per row.
+ * cache, masked attention over the tree tokens, log-sum-exp merge into out / lse.  It runs
+ * as two launches: the cached-key kernel (some extra workgroups of which build the mask),
+ * then one kernel that does the tree attention and the merge per query row.
  *
  *   prefix_lens  DEVICE int32[batch]; values are clamped into [0, max_prefix_len].
  *                A sequence with prefix length 0 attends to its tree tokens only.
