@@ -126,6 +126,47 @@ def bench_accept_commit(args, w):
         "cpu_baseline": cpu}))
 
 
+class ClockSampler:
+    """Samples the shader clock and board power the driver reports (sysfs) while a timed region runs."""
+
+    def __init__(self, period_s=0.002):
+        import glob
+        import threading
+        self.sclk_files = glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")[:1]
+        self.power_files = glob.glob("/sys/class/drm/card*/device/hwmon/*/power1_input")[:1]
+        self.period, self.sclk, self.power = period_s, [], []
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        while not self._stop.is_set():
+            try:
+                for f in self.sclk_files:
+                    for line in open(f).read().splitlines():
+                        if line.rstrip().endswith("*"):
+                            self.sclk.append(int("".join(ch for ch in line.split(":")[1] if ch.isdigit())))
+                for f in self.power_files:
+                    self.power.append(int(open(f).read()) / 1e6)
+            except (OSError, ValueError, IndexError):
+                pass
+            self._stop.wait(self.period)
+
+    def __enter__(self):
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._thread.join(timeout=1.0)
+
+    def summary(self):
+        def stats(v):
+            v = sorted(v)
+            return {"n": len(v), "min": v[0], "median": v[len(v) // 2], "max": v[-1]} if v else None
+        return {"sclk_mhz": stats(self.sclk), "power_w": stats(self.power),
+                "source": "sysfs pp_dpm_sclk / hwmon power1_input, sampled during the timed steps"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -222,11 +263,12 @@ def main():
     for i in range(args.warmup):
         call(i)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        call(i)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    with ClockSampler() as sampler:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            call(i)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     us_per_call = wall / args.steps * 1e6
 
     # per-call latency distribution (events around each call)
@@ -368,6 +410,7 @@ def main():
         "call_tflops": fl / us_per_call / 1e6,
         "hot_cache_us": hot_us,
         "practical_peaks": practical,
+        "clocks": sampler.summary(),
         "roofline": roof,
         "cpu_baseline": cpu,
     }
