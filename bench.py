@@ -181,6 +181,10 @@ def main():
                     help="keep the cache in shuffled pages of this many rows and call ls_hybrid_tree_attn_paged")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hot", action="store_true", help="also time with one K/V copy (cache-resident)")
+    ap.add_argument("--token-major", action="store_true",
+                    help="store Q, K, V and out as [B,L,H,D] (each head's row a run of D elements) and pass strides")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time replays of a HIP graph that holds one cycle over the K/V copies")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 device copies of 512 MiB (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -215,14 +219,16 @@ def main():
     if w.kind == "accept":
         return bench_accept_commit(args, w)
     batch = synth.make_batch(w, "iid")
-    db = DeviceBatch(batch)
+    db = DeviceBatch(batch, token_major=args.token_major)
     plens = batch.prefix_lens.tolist()
 
     # cold-cache rotation: independent K/V copies totalling >= 1 GiB
     kv_bytes = db.k_cache.numel() * db.k_cache.element_size() * 2
     n_rot = max(2, -(-(1 << 30) // kv_bytes))
-    k_rot = [db.k_cache] + [db.k_cache.clone() for _ in range(n_rot - 1)]
-    v_rot = [db.v_cache] + [db.v_cache.clone() for _ in range(n_rot - 1)]
+    # (a copy keeps the storage order of its source: same strides for every copy)
+    same_order = lambda x: torch.empty_strided(x.shape, x.stride(), dtype=x.dtype, device=x.device).copy_(x)
+    k_rot = [db.k_cache] + [same_order(db.k_cache) for _ in range(n_rot - 1)]
+    v_rot = [db.v_cache] + [same_order(db.v_cache) for _ in range(n_rot - 1)]
     ws = torch.empty(ls.ls_workspace_bytes(db.desc), dtype=torch.uint8, device="cuda")
     n_splits = ls.ls_prefix_num_splits(db.desc)
     stream = torch.cuda.current_stream()
@@ -232,6 +238,7 @@ def main():
         # the same rows scattered over shuffled pages [page, Hkv, page_size, D]; one table for all copies
         ps = args.page_size
         assert w.kind == "verify" and batch.max_prefix_len % ps == 0, "paged timing: whole pages, verify workloads"
+        assert not args.token_major, "paged timing keeps each page head-major"
         per_seq = batch.max_prefix_len // ps
         n_pages = w.batch * per_seq
         perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(w.seed)).cuda()
@@ -249,7 +256,7 @@ def main():
         v_rot = [to_pages(x) for x in v_rot]
         paged_desc = ls.make_desc(db.q, k_rot[0], v_rot[0], db.k_tree, db.v_tree, db.out, batch.max_prefix_len)
 
-    def call(i, r=None):
+    def call(i, r=None, stream=stream):
         r = i % n_rot if r is None else r
         if table is not None:
             ls.ls_hybrid_tree_attn_paged(paged_desc, db.q, k_rot[r], v_rot[r], table, args.page_size, db.prefix_lens,
@@ -322,6 +329,24 @@ def main():
             call(i, 0)
         torch.cuda.synchronize()
         hot_us = (time.perf_counter() - t0) / args.steps * 1e6
+
+    graph_us = None
+    if args.graph:
+        # one cycle over the K/V copies recorded once; a replay issues it with no host work per call
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            cap = torch.cuda.current_stream()
+            for r in range(n_rot):
+                call(r, r, cap)
+        reps = max(1, args.steps // n_rot)
+        for _ in range(max(1, args.warmup // n_rot)):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) / (reps * n_rot) * 1e6
 
     # what this card reaches in practice: a pure streaming read of 1 GiB, a bf16 MFMA issue loop
     buf = torch.full((1 << 30,), 1, dtype=torch.uint8, device="cuda")
@@ -402,13 +427,14 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q heads / {w.n_kv_heads} kv heads, head_dim "
                                f"{w.head_dim}, prefix {plens}, n_tree {w.n_tree}, seed {w.seed}",
-                   "kv_layout": "[B,Hkv,P,D]" if table is None else f"shuffled pages [page,Hkv,{args.page_size},D]", "n_splits": n_splits, "kv_rotation_copies": n_rot,
+                   "kv_layout": ("[B,P,Hkv,D] (token-major)" if args.token_major else "[B,Hkv,P,D]") if table is None else f"shuffled pages [page,Hkv,{args.page_size},D]", "n_splits": n_splits, "kv_rotation_copies": n_rot,
                    "kv_rotation_bytes": n_rot * kv_bytes},
         "call_us": {"mean_wall": us_per_call, "event_min": float(lat.min()), "event_median": float(np.median(lat)),
                     "event_p90": float(np.percentile(lat, 90))},
         "call_hbm_gbs": bytes_call / us_per_call / 1e3,
         "call_tflops": fl / us_per_call / 1e6,
         "hot_cache_us": hot_us,
+        "graph_replay_us": graph_us,
         "practical_peaks": practical,
         "clocks": sampler.summary(),
         "roofline": roof,
