@@ -44,7 +44,7 @@
  * Query head h reads KV head h / (n_q_heads / n_kv_heads).
  *
  * Supported: dtype bf16, f16 (the precision of the paper's experiments, appendix
- * "Experiments Details") or f32; head_dim 64 or 128; 1 <= n_tree <= 128;
+ * "Experiments Details") or f32; head_dim 64 or 128; 1 <= n_tree <= 512;
  * n_q_heads a multiple of n_kv_heads; 0 <= prefix length <= max_prefix_len.
  * Anything else returns LS_ERR_UNSUPPORTED.
  */
@@ -72,7 +72,7 @@ typedef enum {
 
 typedef enum { LS_BF16 = 0, LS_F32 = 1, LS_F16 = 2 } ls_dtype;
 
-#define LS_MAX_TREE 128
+#define LS_MAX_TREE 512
 
 /* Problem descriptor (host memory, read during the call only). */
 typedef struct {

@@ -20,7 +20,7 @@ LS_OK = 0
 LS_ERR_NULL, LS_ERR_SHAPE, LS_ERR_DTYPE, LS_ERR_STRIDE = -1, -2, -3, -4
 LS_ERR_TREE, LS_ERR_WORKSPACE, LS_ERR_HIP, LS_ERR_UNSUPPORTED = -5, -6, -7, -8
 LS_BF16, LS_F32, LS_F16 = 0, 1, 2
-LS_MAX_TREE = 128
+LS_MAX_TREE = 512
 
 _i32, _i64, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_float
 _vp, _sz = ctypes.c_void_p, ctypes.c_size_t

@@ -2,20 +2,20 @@
 // of the speculation tree (Section 2.1 "Fast Tree Attention", evaluated at T = 0 in Section
 // 4.1) and the move of the accepted tokens' key/value rows into the cache (the cache is
 // updated only once verification is complete, Section 3.2; "KV cache movement" in the
-// appendix "Experiments Details").  Both are latency-bound: a tree has at most 128 nodes.
+// appendix "Experiments Details").  Both are latency-bound: a tree has at most LS_MAX_TREE nodes.
 #include "ls_internal.hpp"
 
 namespace ls {
 
 namespace {
 
-// One workgroup per sequence, one thread per node.
+// One workgroup per sequence; a thread takes nodes tid, tid + blockDim.x, ...
 //   match[i]   node i carries the token the target predicts after its parent
 //   chosen[i]  match[i] and no earlier sibling matches (lowest index wins among equal tokens)
 //   node i is on the accepted path iff every node from i up to, not including, node 0 is
 //   chosen and that walk ends at node 0.  At most one child of a node is chosen, so the
 //   accepted nodes form one root path and a node's position on it is its depth.
-__global__ void __launch_bounds__(LS_MAX_TREE)
+__global__ void __launch_bounds__(256)
 tree_accept_kernel(const int32_t *__restrict__ parents, const int32_t *__restrict__ draft,
                    const int32_t *__restrict__ target, int32_t n_tree, int32_t *__restrict__ path,
                    int32_t *__restrict__ accept_len, int32_t *__restrict__ next_token,
@@ -26,17 +26,17 @@ tree_accept_kernel(const int32_t *__restrict__ parents, const int32_t *__restric
     __shared__ uint8_t match[LS_MAX_TREE];
     __shared__ uint8_t chosen[LS_MAX_TREE];
     __shared__ int32_t len_sh;
+    __shared__ int32_t last_sh;
     const int b = blockIdx.x;
-    const int i = threadIdx.x;
-    const bool live = i < n_tree;
+    const int tid = threadIdx.x;
+    const int step = blockDim.x;
     parents += (size_t)b * n_tree;
     draft += (size_t)b * n_tree;
     target += (size_t)b * n_tree;
     path += (size_t)b * n_tree;
 
     int bad = 0;
-    int32_t my_token = 0;
-    if (live) {
+    for (int i = tid; i < n_tree; i += step) {
         int32_t p = parents[i];
         if (p < -1 || p >= i) {  // not a forest in topological order: treat the node as a root
             bad = 1;
@@ -44,21 +44,23 @@ tree_accept_kernel(const int32_t *__restrict__ parents, const int32_t *__restric
         }
         par[i] = p;
         tgt[i] = target[i];
-        my_token = draft[i];
         path[i] = -1;
     }
-    if (i == 0) len_sh = 0;
+    if (tid == 0) {
+        len_sh = 0;
+        last_sh = 0;
+    }
     __syncthreads();
-    if (live) match[i] = i > 0 && par[i] >= 0 && my_token == tgt[par[i]];
+    for (int i = tid; i < n_tree; i += step) match[i] = i > 0 && par[i] >= 0 && draft[i] == tgt[par[i]];
     __syncthreads();
-    if (live) {
+    for (int i = tid; i < n_tree; i += step) {
         bool first = match[i];
         for (int j = 1; j < i && first; ++j)
             if (par[j] == par[i] && match[j]) first = false;
         chosen[i] = first;
     }
     __syncthreads();
-    if (live) {
+    for (int i = tid; i < n_tree; i += step) {
         int cur = i, depth = 0;
         bool on_path = true;
         while (cur > 0) {  // par[cur] < cur, so this ends after at most i steps
@@ -72,29 +74,18 @@ tree_accept_kernel(const int32_t *__restrict__ parents, const int32_t *__restric
         on_path = on_path && cur == 0;  // a walk that ends at another root is off the path
         if (on_path) {
             path[depth] = i;
+            // depth in the high bits, node in the low ones: the maximum names the deepest accepted node
+            atomicMax(&last_sh, (depth << 16) | i);
             atomicMax(&len_sh, depth + 1);
         }
     }
-    __syncthreads();
-    if (live) {
-        // the deepest accepted node reports the token the target adds itself
-        int cur = i, depth = 0;
-        bool on_path = true;
-        while (cur > 0) {
-            if (!chosen[cur]) {
-                on_path = false;
-                break;
-            }
-            cur = par[cur];
-            ++depth;
-        }
-        if (on_path && cur == 0 && depth + 1 == len_sh) {
-            next_token[b] = tgt[i];
-            accept_len[b] = len_sh;
-        }
-    }
     const int any_bad = __syncthreads_or(bad);
-    if (i == 0 && err_flag) err_flag[b] = any_bad ? 1 : 0;
+    if (tid == 0) {
+        // the deepest accepted node reports the token the target adds itself
+        next_token[b] = tgt[last_sh & 0xffff];
+        accept_len[b] = len_sh;
+        if (err_flag) err_flag[b] = any_bad ? 1 : 0;
+    }
 }
 
 // One workgroup per (sequence, KV head): 16-byte pieces of the accepted rows of K and V are
@@ -121,10 +112,10 @@ kv_commit_kernel(Problem p, int elem_bytes, const int32_t *__restrict__ accept_p
     int n = want < room ? want : room;
     if (tid == 0) n_sh = n;
     __syncthreads();
-    if (tid < n) {
-        const int32_t node = accept_path[(size_t)b * p.n_tree + tid];
-        path[tid] = node;
-        if (node < 0 || node >= p.n_tree) atomicMin(&n_sh, tid);  // stop before the first bad entry
+    for (int t = tid; t < n; t += blockDim.x) {
+        const int32_t node = accept_path[(size_t)b * p.n_tree + t];
+        path[t] = node;
+        if (node < 0 || node >= p.n_tree) atomicMin(&n_sh, t);  // stop before the first bad entry
     }
     __syncthreads();
     n = n_sh;
@@ -160,7 +151,8 @@ hipError_t launch_tree_accept(const int32_t *parents, const int32_t *draft_token
                               int32_t batch, int32_t n_tree, int32_t *accept_path, int32_t *accept_len,
                               int32_t *next_token, int32_t *err_flag, hipStream_t stream)
 {
-    hipLaunchKernelGGL(tree_accept_kernel, dim3(batch), dim3(LS_MAX_TREE), 0, stream, parents, draft_tokens,
+    const int threads = n_tree <= 64 ? 64 : (n_tree <= 128 ? 128 : 256);
+    hipLaunchKernelGGL(tree_accept_kernel, dim3(batch), dim3(threads), 0, stream, parents, draft_tokens,
                        target_tokens, n_tree, accept_path, accept_len, next_token, err_flag);
     return hipGetLastError();
 }

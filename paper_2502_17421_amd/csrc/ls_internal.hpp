@@ -107,36 +107,33 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// The tree-mask rows of one sequence, computed by the first n_tree threads of a workgroup
-// (all threads of the workgroup must call it; it synchronises them once).
+// The tree-mask rows of one sequence, computed by the n_threads threads of a workgroup, node
+// tid, tid + n_threads, ... each (all threads of the workgroup must call it; it synchronises
+// them once).  A row is built one 64-bit word at a time from the highest word down: the chain
+// index strictly decreases, so the walk visits the words in that order and ends after at most
+// `node` steps whatever the array holds; an entry outside {-1} u [0, j) ends the walk and is
+// reported.
 __device__ __forceinline__ void build_tree_mask_rows(const int32_t *__restrict__ par, int32_t n_tree,
                                                      uint64_t *__restrict__ mask_rows,
-                                                     int32_t *__restrict__ err_word, int tid)
+                                                     int32_t *__restrict__ err_word, int tid, int n_threads)
 {
-    constexpr int WORDS = LS_MAX_TREE / 64;
-    uint64_t bits[WORDS];
-#pragma unroll
-    for (int w = 0; w < WORDS; ++w) bits[w] = 0;
+    const int words = (n_tree + 63) >> 6;
     int bad = 0;
-    int j = tid < n_tree ? tid : -1;
-    // the chain index strictly decreases, so the walk ends after at most tid steps whatever
-    // the array holds; an entry outside {-1} u [0, j) ends the walk and is reported
-    while (j >= 0) {
-#pragma unroll
-        for (int w = 0; w < WORDS; ++w)
-            if ((j >> 6) == w) bits[w] |= (uint64_t)1 << (j & 63);
-        int p = par[j];
-        if (p < -1 || p >= j) {
-            bad = 1;
-            p = -1;
+    for (int node = tid; node < n_tree; node += n_threads) {
+        int j = node;
+        for (int w = words - 1; w >= 0; --w) {
+            uint64_t bits = 0;
+            while (j >= 0 && (j >> 6) == w) {
+                bits |= (uint64_t)1 << (j & 63);
+                int p = par[j];
+                if (p < -1 || p >= j) {
+                    bad = 1;
+                    p = -1;
+                }
+                j = p;
+            }
+            mask_rows[(size_t)node * words + w] = bits;
         }
-        j = p;
-    }
-    if (tid < n_tree) {
-        const int words = (n_tree + 63) >> 6;
-#pragma unroll
-        for (int w = 0; w < WORDS; ++w)
-            if (w < words) mask_rows[(size_t)tid * words + w] = bits[w];
     }
     const int any_bad = __syncthreads_or(bad);
     if (tid == 0 && err_word) *err_word = any_bad ? 1 : 0;

@@ -194,7 +194,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
         const int words = (p.n_tree + 63) >> 6;
         build_tree_mask_rows(mask_job.parents + (size_t)mb * p.n_tree, p.n_tree,
                              mask_job.mask + (size_t)mb * p.n_tree * words,
-                             mask_job.err_flag ? mask_job.err_flag + mb : nullptr, tid);
+                             mask_job.err_flag ? mask_job.err_flag + mb : nullptr, tid, (int)blockDim.x);
         return;
     }
     const int split = blockIdx.x % plan.n_splits;
@@ -636,7 +636,6 @@ hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &o
 {
     constexpr int lds_bytes = NS * 2 * TK * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a compute unit");
-    static_assert(NW * 64 >= LS_MAX_TREE, "the mask workgroups need one thread per tree token");
     auto kernel = prefix_mfma_kernel<D, NW, NS, F16>;
     static hipError_t attr = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  lds_bytes);

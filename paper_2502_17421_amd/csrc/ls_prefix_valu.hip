@@ -50,7 +50,7 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job)
         const int words = (p.n_tree + 63) >> 6;
         build_tree_mask_rows(mask_job.parents + (size_t)mb * p.n_tree, p.n_tree,
                              mask_job.mask + (size_t)mb * p.n_tree * words,
-                             mask_job.err_flag ? mask_job.err_flag + mb : nullptr, tid);
+                             mask_job.err_flag ? mask_job.err_flag + mb : nullptr, tid, (int)blockDim.x);
         return;
     }
     const int split = blockIdx.x;
@@ -215,7 +215,6 @@ hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan
     // the mask slice offers n_splits * n_qblocks workgroups: enough for the batch?
     if (with_mask && (int64_t)plan.n_splits * n_qblocks < p.batch) return hipErrorInvalidValue;
     const dim3 block(256), grid(plan.n_splits, n_qblocks, p.batch * p.n_kv_heads + (with_mask ? 1 : 0));
-    static_assert(256 >= LS_MAX_TREE, "the mask workgroups need one thread per tree token");
 #define LS_PV_CASE(T, DD) \
     hipLaunchKernelGGL((prefix_valu_kernel<T, DD>), grid, block, 0, stream, p, plan, out, mask_job)
     if (dtype == LS_BF16 && p.head_dim == 128) LS_PV_CASE(uint16_t, 128);

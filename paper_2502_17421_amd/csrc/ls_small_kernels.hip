@@ -5,22 +5,23 @@
 namespace ls {
 
 // --------------------------------------------------------------------------- (a) ----
-// Tree mask: one workgroup per sequence; thread i walks the parent chain of node i and sets
+// Tree mask: one workgroup per sequence; a thread walks the parent chain of its node and sets
 // one bit per node met, itself included.  err_flag[b] is written 0 or 1 on every launch.
-__global__ void __launch_bounds__(LS_MAX_TREE)
+__global__ void __launch_bounds__(256)
 tree_mask_kernel(const int32_t *__restrict__ parents, int32_t n_tree, uint64_t *__restrict__ mask,
                  int32_t *__restrict__ err_flag)
 {
     const int b = blockIdx.x;
     const int words = (n_tree + 63) >> 6;
     build_tree_mask_rows(parents + (size_t)b * n_tree, n_tree, mask + (size_t)b * n_tree * words,
-                         err_flag ? err_flag + b : nullptr, threadIdx.x);
+                         err_flag ? err_flag + b : nullptr, threadIdx.x, blockDim.x);
 }
 
 hipError_t launch_tree_mask(const int32_t *parents, int32_t batch, int32_t n_tree, uint64_t *mask,
                             int32_t *err_flag, hipStream_t stream)
 {
-    hipLaunchKernelGGL(tree_mask_kernel, dim3(batch), dim3(LS_MAX_TREE), 0, stream, parents, n_tree, mask, err_flag);
+    const int threads = n_tree <= 64 ? 64 : (n_tree <= 128 ? 128 : 256);
+    hipLaunchKernelGGL(tree_mask_kernel, dim3(batch), dim3(threads), 0, stream, parents, n_tree, mask, err_flag);
     return hipGetLastError();
 }
 

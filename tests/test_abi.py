@@ -95,7 +95,7 @@ def test_validate_desc_codes():
     assert ls.ls_validate_desc(x) == ls.LS_ERR_DTYPE
     x = good_desc(); x.head_dim = 96
     assert ls.ls_validate_desc(x) == ls.LS_ERR_UNSUPPORTED
-    x = good_desc(); x.n_tree = 129
+    x = good_desc(); x.n_tree = 513
     assert ls.ls_validate_desc(x) == ls.LS_ERR_UNSUPPORTED
     x = good_desc(); x.kc_stride[2] = 132          # 264-byte rows: not 16-byte aligned
     assert ls.ls_validate_desc(x) == ls.LS_ERR_STRIDE
@@ -154,7 +154,7 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_cache_attn(dp, one, odd, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_STRIDE
     assert L.ls_build_tree_mask(None, 1, 4, one, None, None) == ls.LS_ERR_NULL
     assert L.ls_build_tree_mask(one, 1, 0, one, None, None) == ls.LS_ERR_SHAPE
-    assert L.ls_build_tree_mask(one, 1, 129, one, None, None) == ls.LS_ERR_UNSUPPORTED
+    assert L.ls_build_tree_mask(one, 1, 513, one, None, None) == ls.LS_ERR_UNSUPPORTED
     assert L.ls_prefix_attn_splitkv(dp, one, one, one, None, 0, ls.LS_F32, one, one, None) == ls.LS_ERR_NULL
     assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, -1, ls.LS_F32, one, one, None) == ls.LS_ERR_SHAPE
     assert L.ls_prefix_attn_splitkv(dp, one, one, one, one, 2, 5, one, one, None) == ls.LS_ERR_DTYPE
@@ -165,7 +165,7 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_lse_merge(dp, 2, 9, one, one, one, one, None) == ls.LS_ERR_DTYPE
     assert L.ls_tree_accept_greedy(one, one, None, 1, 4, one, one, one, None, None) == ls.LS_ERR_NULL
     assert L.ls_tree_accept_greedy(one, one, one, 0, 4, one, one, one, None, None) == ls.LS_ERR_SHAPE
-    assert L.ls_tree_accept_greedy(one, one, one, 1, 129, one, one, one, None, None) == ls.LS_ERR_UNSUPPORTED
+    assert L.ls_tree_accept_greedy(one, one, one, 1, 513, one, one, one, None, None) == ls.LS_ERR_UNSUPPORTED
     assert L.ls_kv_commit(dp, one, one, one, one, one, None, one, None, None, None) == ls.LS_ERR_NULL
     assert L.ls_kv_commit(dp, one, one, one, one, one, one, one, one, None, None) == ls.LS_ERR_NULL   # aliasing lengths
     assert L.ls_kv_commit(dp, one, odd, one, one, one, one, one, None, None, None) == ls.LS_ERR_STRIDE

@@ -35,7 +35,8 @@ def run_accept(parents, draft, target):
 
 
 @pytest.mark.parametrize("t,vocab,p_follow", [(1, 5, 0.5), (7, 3, 0.5), (64, 4, 0.8), (69, 32000, 0.7),
-                                              (128, 2, 0.9), (128, 32000, 0.95)])
+                                              (128, 2, 0.9), (128, 32000, 0.95), (129, 3, 0.9), (300, 32000, 0.97),
+                                              (512, 2, 0.95), (512, 32000, 0.99)])
 def test_acceptance_matches_oracle(t, vocab, p_follow):
     rng = np.random.default_rng(8100 + t + vocab)
     b = 9

@@ -39,11 +39,11 @@ def small(name, prefix, variant="iid", **over):
 
 # ------------------------------------------------------------------------- (a) mask ----
 
-@pytest.mark.parametrize("n_tree", [1, 2, 5, 63, 64, 65, 100, 128])
+@pytest.mark.parametrize("n_tree", [1, 2, 5, 63, 64, 65, 100, 128, 129, 192, 256, 257, 300, 511, 512])
 def test_mask_bit_exact(n_tree):
     rng = np.random.default_rng(500 + n_tree)
     trees = [synth.tree_uniform(rng, n_tree), synth.tree_chain(n_tree), synth.tree_star(n_tree),
-             synth.tree_constrained(rng, n_tree, 10, 4) if n_tree <= 128 else synth.tree_chain(n_tree)]
+             synth.tree_constrained(rng, n_tree, 10, 4)]
     forest = synth.tree_uniform(rng, n_tree)
     forest[rng.integers(0, n_tree, size=3)] = -1
     trees.append(forest)

@@ -354,7 +354,7 @@ def bits_of(row):
     return [j for w, word in enumerate(row) for j in range(64 * w, 64 * w + 64) if (int(word) >> (j % 64)) & 1]
 
 
-@pytest.mark.parametrize("t", [1, 5, 64, 65, 100, 128])
+@pytest.mark.parametrize("t", [1, 5, 64, 65, 100, 128, 129, 300, 512])
 def test_mask_properties(t):
     rng = np.random.default_rng(200 + t)
     parents = synth.tree_uniform(rng, t)
