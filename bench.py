@@ -177,7 +177,7 @@ def main():
     ap.add_argument("--workload", default="C3",
                     help="C1..C5 (the headline metric is quoted on C3); D1, D2: cross-attention over the cache only; "
                          "A3, A5: greedy acceptance + KV commit; W1: draft self-attention; H3: C3 in fp16; "
-                         "L3: C3 with a 256-node tree")
+                         "L3: C3 with a 256-node tree; B3: C3 with the 68-node beam tree")
     ap.add_argument("--page-size", type=int, default=0,
                     help="keep the cache in shuffled pages of this many rows and call ls_hybrid_tree_attn_paged")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -188,7 +188,11 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     // Linear workgroup index: key split fastest, then query block, then (sequence, KV head).
     // Workgroups past that range (one per sequence, present only in the whole-path launch)
     // build the tree mask, which the kernel that follows this one consumes.
-    const int n_main = plan.n_splits * n_qblocks * p.batch * p.n_kv_heads;
+    // Per (sequence, KV head): the full query blocks, n_splits workgroups each, then (if it is cut
+    // differently) the last, light query block with rem_splits workgroups.
+    const int n_qb_even = plan.rem_splits ? n_qblocks - 1 : n_qblocks;
+    const int per_unit = n_qb_even * plan.n_splits + plan.rem_splits;
+    const int n_main = per_unit * p.batch * p.n_kv_heads;
     if ((int)blockIdx.x >= n_main) {
         const int mb = blockIdx.x - n_main;
         const int words = (p.n_tree + 63) >> 6;
@@ -197,17 +201,20 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
                              mask_job.err_flag ? mask_job.err_flag + mb : nullptr, tid, (int)blockDim.x);
         return;
     }
-    const int split = blockIdx.x % plan.n_splits;
-    const int qblock = (blockIdx.x / plan.n_splits) % n_qblocks;
-    const int bz = blockIdx.x / (plan.n_splits * n_qblocks);
+    const int bz = blockIdx.x / per_unit;
+    const int in_unit = blockIdx.x % per_unit;
+    const bool light = in_unit >= n_qb_even * plan.n_splits;
+    const int split = light ? in_unit - n_qb_even * plan.n_splits : in_unit % plan.n_splits;
+    const int qblock = light ? n_qb_even : in_unit / plan.n_splits;
+    const int split_len = light ? plan.rem_split_len : plan.split_len;
     const int b = bz / p.n_kv_heads;
     const int g = bz % p.n_kv_heads;
     const int rows_kv = p.group * p.n_tree;
 
     int plen = p.prefix_lens[b];
     plen = plen < 0 ? 0 : (plen > p.max_prefix_len ? p.max_prefix_len : plen);
-    const int k_lo = split * plan.split_len;
-    int k_hi = k_lo + plan.split_len;
+    const int k_lo = split * split_len;
+    int k_hi = k_lo + split_len;
     k_hi = k_hi > plen ? plen : k_hi;
 
     // The query row of this lane.
@@ -217,6 +224,10 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     const int ti = q_ok ? m_row % p.n_tree : 0;
     const size_t part_row = out.row((size_t)b * p.n_q_heads + hq, split, p.n_tree, ti);
 
+    if (light && split == 0 && lh == 0 && q_ok) {  // the parts this query block does not produce
+        for (int s = plan.rem_splits; s < plan.n_splits; ++s)
+            out.lse[out.row((size_t)b * p.n_q_heads + hq, s, p.n_tree, ti)] = -INFINITY;
+    }
     if (k_lo >= k_hi) {  // empty split: weight zero in the merge
         if (lh == 0 && q_ok) out.lse[part_row] = -INFINITY;
         return;
@@ -643,7 +654,10 @@ hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &o
     const int rows_kv = p.group * p.n_tree;
     const int rows_wg = NW * 32;
     const int n_qblocks = (rows_kv + rows_wg - 1) / rows_wg;
-    const int64_t n_main = (int64_t)plan.n_splits * n_qblocks * p.batch * p.n_kv_heads;
+    if (plan.rem_splits < 0 || plan.rem_splits > plan.n_splits || (plan.rem_splits && n_qblocks < 2))
+        return hipErrorInvalidValue;
+    const int64_t per_unit = (int64_t)plan.n_splits * (plan.rem_splits ? n_qblocks - 1 : n_qblocks) + plan.rem_splits;
+    const int64_t n_main = per_unit * p.batch * p.n_kv_heads;
     const int64_t n_blocks = n_main + (mask_job.parents ? p.batch : 0);
     if (n_blocks > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), lds_bytes, stream, p, plan, out, mask_job,

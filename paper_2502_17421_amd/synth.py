@@ -59,6 +59,9 @@ WORKLOADS = {
     # the C3 and C5 shapes; "kind" accept.
     "A3": Workload("A3", "bf16", 1, 32, 8, 128, 64, 32768, 32768, 8, 4, 1023, "accept"),
     "A5": Workload("A5", "bf16", 4, 40, 8, 128, 128, 16384, 65536, 10, 4, 1025, "accept"),
+    # The C3 shape under the paper's own tree: five beam steps of widths 4, 16, 16, 16, 16 (Appendix
+    # "Experiments Details") = 68 nodes, 272 query rows per KV head: one full query block + 16 rows.
+    "B3": Workload("B3", "bf16", 1, 32, 8, 128, 68, 32768, 32768, 5, 16, 1063),
     # The C3 shape under a speculation tree four times the size (256 nodes, 1024 query rows per
     # KV head): the regime of large static trees, bound by the matrix cores rather than by HBM.
     "L3": Workload("L3", "bf16", 1, 32, 8, 128, 256, 32768, 32768, 12, 4, 1053),
