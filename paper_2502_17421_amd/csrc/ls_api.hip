@@ -185,6 +185,19 @@ SplitPlan plan_call(const ls_desc &d)
     const int64_t budget = compute_units() / units;  // workgroups per (sequence, KV head) in one round
     if (units * n_qb * plan.n_splits > compute_units() || budget < n_qb) return plan;
     const int64_t max_p = d.max_prefix_len;
+    // the search below costs a few microseconds of host time: remember the last shape's answer
+    struct Memo {
+        int32_t key[7];
+        SplitPlan plan;
+    };
+    static thread_local Memo memo = {{0, 0, 0, 0, 0, -1, 0}, {0, 0, 0, 0}};
+    const int32_t key[7] = {d.batch, d.n_q_heads, d.n_kv_heads, d.n_tree, d.max_prefix_len, d.dtype, compute_units()};
+    if (std::memcmp(key, memo.key, sizeof(key)) == 0) return memo.plan;
+    auto remember = [&](const SplitPlan &pl) {
+        std::memcpy(memo.key, key, sizeof(key));
+        memo.plan = pl;
+        return pl;
+    };
     auto tiles = [&](int64_t s) { return ((max_p + s - 1) / s + kTile - 1) / kTile; };
     double best = 0.0;
     int64_t best_f = 0, best_r = 0;
@@ -201,14 +214,14 @@ SplitPlan plan_call(const ls_desc &d)
             }
         }
     }
-    if (best_f == 0 || best_r == best_f) return plan;
+    if (best_f == 0 || best_r == best_f) return remember(plan);
     auto length = [&](int64_t s) { return (int32_t)(((max_p + s - 1) / s + kTile - 1) / kTile * kTile); };
-    plan.split_len = length(best_f);
-    plan.n_splits = (int32_t)((max_p + plan.split_len - 1) / plan.split_len);
-    plan.rem_split_len = length(best_r);
-    plan.rem_splits = (int32_t)((max_p + plan.rem_split_len - 1) / plan.rem_split_len);
-    if (plan.rem_splits >= plan.n_splits) return plan_splits(d, 0);
-    return plan;
+    SplitPlan uneven = plan;
+    uneven.split_len = length(best_f);
+    uneven.n_splits = (int32_t)((max_p + uneven.split_len - 1) / uneven.split_len);
+    uneven.rem_split_len = length(best_r);
+    uneven.rem_splits = (int32_t)((max_p + uneven.rem_split_len - 1) / uneven.rem_split_len);
+    return remember(uneven.rem_splits >= uneven.n_splits ? plan : uneven);
 }
 
 }  // namespace ls
