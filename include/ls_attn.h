@@ -111,14 +111,17 @@ int ls_validate_parents_host(const int32_t *parents, int32_t batch, int32_t n_tr
 
 /*
  * Number of key-axis splits the library would pick for the cached part of this
- * problem (>= 1; depends only on the descriptor, so it is stable across calls).
+ * problem (>= 1; depends only on the descriptor, so it is stable across calls): what
+ * ls_prefix_attn_splitkv uses for n_splits = 0.  The whole-path calls may cut the keys
+ * differently (more pieces for the full 256-row query blocks of a KV head, fewer for a light
+ * last block); their workspace size accounts for that.
  */
 int ls_prefix_num_splits(const ls_desc *desc, int32_t *n_splits_out);
 
 /*
  * Bytes of DEVICE workspace ls_hybrid_tree_attn needs for this descriptor:
- * the tree mask, one error word per sequence, and the n_splits partial outputs (stored in
- * the problem's dtype) and LSEs of the cached part.
+ * the tree mask, one error word per sequence, and the partial outputs (stored in the
+ * problem's dtype) and LSEs of the cached part, one per key split of the call's own schedule.
  * The workspace must be 256-byte aligned.
  */
 int ls_workspace_bytes(const ls_desc *desc, size_t *bytes_out);
