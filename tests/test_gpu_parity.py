@@ -471,7 +471,7 @@ def test_scale_override_and_group_mapping():
 
 # ------------------------------------------------ the benchmark shapes at full size ----
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "B3", "L3", "H3"])
 def test_full_size_sampled_rows(name):
     w = synth.WORKLOADS[name]
     say(f"{name}: drawing inputs")
@@ -487,7 +487,7 @@ def test_full_size_sampled_rows(name):
     rows, ro, rl = oracle_full(batch, rows_per_seq=96, rng=rng)
     got_o = np.stack([out[b, rows[b, :, 0], rows[b, :, 1]] for b in range(w.batch)])
     got_l = np.stack([lse[b, rows[b, :, 0], rows[b, :, 1]] for b in range(w.batch)])
-    say(gates(got_o, got_l, ro, rl, "bf16", f"{name} full size, 96 sampled rows per sequence"))
+    say(gates(got_o, got_l, ro, rl, w.dtype, f"{name} full size, 96 sampled rows per sequence"))
     # a property that holds for every row at any size: with i.i.d. N(0,1) logits the
     # log-sum-exp sits close to ln(number of visible keys) + 1/2
     expect = np.log(batch.prefix_lens.astype(np.float64))[:, None, None] + 0.5
