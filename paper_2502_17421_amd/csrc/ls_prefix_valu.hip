@@ -136,14 +136,21 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job)
         float s[4];
 #pragma unroll
         for (int a = 0; a < 4; ++a) s[a] = 0.f;
-#pragma unroll 4
-        for (int dd = 0; dd < D; dd += 4) {
-            const float4 q4 = *(const float4 *)&q_s[r][dd];
+        // 16 head-dim elements per step: all 20 LDS reads of a step are issued before the first
+        // product, so their latencies overlap instead of adding up
+        for (int dd = 0; dd < D; dd += 16) {
+            float4 q4[4], k4[4][4];
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const float4 k4 = *(const float4 *)&k_s[c + 8 * a][dd];
-                s[a] += q4.x * k4.x + q4.y * k4.y + q4.z * k4.z + q4.w * k4.w;
+            for (int u = 0; u < 4; ++u) {
+                q4[u] = *(const float4 *)&q_s[r][dd + 4 * u];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) k4[a][u] = *(const float4 *)&k_s[c + 8 * a][dd + 4 * u];
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    s[a] += q4[u].x * k4[a][u].x + q4[u].y * k4[a][u].y + q4[u].z * k4[a][u].z + q4[u].w * k4[a][u].w;
         }
         float tmax = -INFINITY;
 #pragma unroll
@@ -174,19 +181,22 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job)
             acc[i].w *= alpha;
         }
         __syncthreads();  // p_s row r complete
-#pragma unroll 2
-        for (int jj = 0; jj < TK; jj += 4) {
+        for (int jj = 0; jj < TK; jj += 4) {  // likewise: the reads of four keys first, then the products
             const float4 p4 = *(const float4 *)&p_s[r][jj];
             const float pj[4] = {p4.x, p4.y, p4.z, p4.w};
+            float4 v4[4][D / 32];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < D / 32; ++i) v4[u][i] = *(const float4 *)&v_s[jj + u][4 * (c + 8 * i)];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int i = 0; i < D / 32; ++i) {
-                    const float4 v4 = *(const float4 *)&v_s[jj + u][4 * (c + 8 * i)];
-                    acc[i].x += pj[u] * v4.x;
-                    acc[i].y += pj[u] * v4.y;
-                    acc[i].z += pj[u] * v4.z;
-                    acc[i].w += pj[u] * v4.w;
+                    acc[i].x += pj[u] * v4[u][i].x;
+                    acc[i].y += pj[u] * v4[u][i].y;
+                    acc[i].z += pj[u] * v4[u][i].z;
+                    acc[i].w += pj[u] * v4[u][i].w;
                 }
         }
     }
