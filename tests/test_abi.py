@@ -56,6 +56,50 @@ def test_descriptor_layout_matches_c(tmp_path):
                    d.kc_stride.offset, d.vt_stride.offset]
 
 
+C_CALLER = r"""
+#include <stdio.h>
+#include <string.h>
+#include "ls_attn.h"
+/* a plain C caller: fills a descriptor for [B,H,L,D] tensors and asks the host-only entry points */
+int main(void)
+{
+    ls_desc d;
+    memset(&d, 0, sizeof d);
+    d.batch = 1; d.n_q_heads = 32; d.n_kv_heads = 8; d.head_dim = 128; d.n_tree = 64; d.max_prefix_len = 32768;
+    d.dtype = LS_BF16;
+    const int64_t hq = 32, hkv = 8, t = 64, p = 32768, dd = 128;
+    int64_t *s[6] = {d.q_stride, d.o_stride, d.kc_stride, d.vc_stride, d.kt_stride, d.vt_stride};
+    const int64_t heads[6] = {hq, hq, hkv, hkv, hkv, hkv}, rows[6] = {t, t, p, p, t, t};
+    for (int i = 0; i < 6; ++i) { s[i][0] = heads[i] * rows[i] * dd; s[i][1] = rows[i] * dd; s[i][2] = dd; }
+    int32_t n_splits = 0, split_len = 0;
+    size_t bytes = 0;
+    int rc = ls_validate_desc(&d);
+    if (rc == LS_OK) rc = ls_prefix_num_splits(&d, &n_splits);
+    if (rc == LS_OK) rc = ls_prefix_split_len(&d, 0, &split_len);
+    if (rc == LS_OK) rc = ls_workspace_bytes(&d, &bytes);
+    d.head_dim = 80;
+    printf("%d %d %d %zu %d %s\n", rc, n_splits, split_len, bytes, ls_validate_desc(&d), ls_status_string(LS_ERR_UNSUPPORTED));
+    return ls_version() >= 100 ? 0 : 1;
+}
+"""
+
+
+def test_a_plain_c_program_links_and_calls_the_library(tmp_path):
+    """The boundary is a C ABI: a C99 translation unit that includes only the header links
+    against the shared library and gets the same answers as the Python binding."""
+    src = tmp_path / "caller.c"
+    src.write_text(C_CALLER)
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(ls.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-lls_attn", "-Wl,--allow-shlib-undefined", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=5)
+    d = good_desc(hq=32, hkv=8, t=64, p=32768)
+    assert [int(x) for x in out[:5]] == [ls.LS_OK, ls.ls_prefix_num_splits(d), ls.ls_prefix_split_len(d, 0),
+                                         ls.ls_workspace_bytes(d), ls.LS_ERR_UNSUPPORTED]
+    assert out[5].strip() == ls.ls_status_string(ls.LS_ERR_UNSUPPORTED)
+
+
 def test_version_and_status_strings():
     assert ls.ls_version() >= 100
     seen = set()
