@@ -147,6 +147,19 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q,
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same for one sequence whose prefix length the host knows (the form in which Section 3.3
+ * states the problem: one main sequence, one set of speculative tokens).  desc->batch must be
+ * 1 and 0 <= prefix_len <= desc->max_prefix_len (LS_ERR_SHAPE otherwise); the length travels
+ * as a kernel argument, no device array is read.  Workspace as for ls_hybrid_tree_attn with
+ * the same descriptor; results are bit-identical to that call with prefix_lens[0] = prefix_len.
+ */
+int ls_hybrid_tree_attn_single(const ls_desc *desc, const void *q,
+                               const void *k_cache, const void *v_cache, int32_t prefix_len,
+                               const void *k_tree, const void *v_tree, const int32_t *parents,
+                               void *out, float *lse,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Unmasked attention of the query rows over the cached keys only, merged over the key
  * splits: out = o_cache, lse = LSE_cache of the appendix.  This is the cross-attention over
  * the target model's KV cache that the draft model of Section 3.1 runs at every drafting

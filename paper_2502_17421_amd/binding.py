@@ -65,6 +65,7 @@ def lib() -> ctypes.CDLL:
     L.ls_workspace_bytes.argtypes = [dp, ctypes.POINTER(_sz)]
     L.ls_workspace_error.argtypes = [dp, _vp, ctypes.POINTER(_vp)]
     L.ls_hybrid_tree_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.ls_hybrid_tree_attn_single.argtypes = [dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_cache_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_build_tree_mask.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
     L.ls_prefix_attn_splitkv.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
@@ -79,7 +80,8 @@ def lib() -> ctypes.CDLL:
     L.ls_probe_mfma_loop.argtypes = [_i32, _vp, ctypes.POINTER(ctypes.c_int64), _vp]
     L.ls_kv_commit_paged.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
     for name in ("ls_validate_desc", "ls_validate_parents_host", "ls_prefix_num_splits", "ls_prefix_split_len",
-                 "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_cache_attn", "ls_build_tree_mask",
+                 "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_hybrid_tree_attn_single",
+                 "ls_cache_attn", "ls_build_tree_mask",
                  "ls_prefix_attn_splitkv", "ls_tree_attn_masked", "ls_lse_merge", "ls_tree_accept_greedy",
                  "ls_kv_commit", "ls_hybrid_tree_attn_paged", "ls_cache_attn_paged",
                  "ls_kv_commit_paged", "ls_probe_stream_read", "ls_probe_mfma_loop"):
@@ -200,6 +202,18 @@ def ls_hybrid_tree_attn(desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree, 
                                                         workspace.element_size()), _stream(stream))
     if check:
         _check(st, "ls_hybrid_tree_attn")
+    return int(st)
+
+
+def ls_hybrid_tree_attn_single(desc, q, k_cache, v_cache, prefix_len, k_tree, v_tree, parents, out, lse, workspace,
+                               stream=None, check: bool = True) -> int:
+    """One sequence (desc.batch == 1), prefix length as a host integer."""
+    st = lib().ls_hybrid_tree_attn_single(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), int(prefix_len),
+                                          _ptr(k_tree), _ptr(v_tree), _ptr(parents), _ptr(out), _ptr(lse),
+                                          _ptr(workspace), _sz(0 if workspace is None else workspace.numel() *
+                                                               workspace.element_size()), _stream(stream))
+    if check:
+        _check(st, "ls_hybrid_tree_attn_single")
     return int(st)
 
 

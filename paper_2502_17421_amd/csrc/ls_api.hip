@@ -62,6 +62,7 @@ Problem make_problem(const ls_desc &d, const void *q, const void *kc, const void
     p.k_tree = kt;
     p.v_tree = vt;
     p.prefix_lens = plens;
+    p.prefix_len_all = d.max_prefix_len;
     p.batch = d.batch;
     p.n_q_heads = d.n_q_heads;
     p.n_kv_heads = d.n_kv_heads;
@@ -361,14 +362,19 @@ int ls_lse_merge(const ls_desc *desc, int32_t n_parts, int32_t part_dtype, const
                : LS_ERR_HIP;
 }
 
-int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
-                        const int32_t *prefix_lens, const void *k_tree, const void *v_tree,
-                        const int32_t *parents, void *out, float *lse, void *workspace, size_t workspace_bytes,
-                        void *stream)
+}  // extern "C"
+
+namespace {
+// The whole path for a contiguous cache.  prefix_lens: device array, or nullptr with every
+// sequence holding prefix_len_all cached rows.
+int hybrid_contiguous(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                      const int32_t *prefix_lens, int32_t prefix_len_all, const void *k_tree, const void *v_tree,
+                      const int32_t *parents, void *out, float *lse, void *workspace, size_t workspace_bytes,
+                      void *stream)
 {
     const int rc = validate(desc);
     if (rc) return rc;
-    if (!q || !prefix_lens || !k_tree || !v_tree || !parents || !out || !lse) return LS_ERR_NULL;
+    if (!q || !k_tree || !v_tree || !parents || !out || !lse) return LS_ERR_NULL;
     if (desc->max_prefix_len > 0 && (!k_cache || !v_cache)) return LS_ERR_NULL;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_tree) || !aligned16(v_tree) ||
         !aligned16(out))
@@ -383,7 +389,8 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache,
     float *lse_parts = (float *)(base + w.off_lse);
     void *o_parts = base + w.off_o;
     hipStream_t s = (hipStream_t)stream;
-    const Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree);
+    Problem p = make_problem(*desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree);
+    p.prefix_len_all = prefix_len_all;
 
     // (b) cached keys -> parts [0, n_splits), stored in the problem's dtype; on the MFMA path
     // the same launch carries the workgroups of (a), the tree mask
@@ -404,6 +411,29 @@ int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache,
     if (launch_tree_merge(p, desc->dtype, mask, cache_out, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)
         return LS_ERR_HIP;
     return LS_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int ls_hybrid_tree_attn(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                        const int32_t *prefix_lens, const void *k_tree, const void *v_tree,
+                        const int32_t *parents, void *out, float *lse, void *workspace, size_t workspace_bytes,
+                        void *stream)
+{
+    if (!prefix_lens) return LS_ERR_NULL;
+    return hybrid_contiguous(desc, q, k_cache, v_cache, prefix_lens, 0, k_tree, v_tree, parents, out, lse, workspace,
+                             workspace_bytes, stream);
+}
+
+int ls_hybrid_tree_attn_single(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                               int32_t prefix_len, const void *k_tree, const void *v_tree, const int32_t *parents,
+                               void *out, float *lse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!desc) return LS_ERR_NULL;
+    if (desc->batch != 1 || prefix_len < 0 || prefix_len > desc->max_prefix_len) return LS_ERR_SHAPE;
+    return hybrid_contiguous(desc, q, k_cache, v_cache, nullptr, prefix_len, k_tree, v_tree, parents, out, lse,
+                             workspace, workspace_bytes, stream);
 }
 
 int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,

@@ -22,7 +22,8 @@ struct Problem {
     const void *v_cache;
     const void *k_tree;
     const void *v_tree;
-    const int32_t *prefix_lens;
+    const int32_t *prefix_lens;  // device, one per sequence; nullptr: every sequence has prefix_len_all rows
+    int32_t prefix_len_all;
     // Paged cache (block_table != nullptr): cache row r of sequence b lives in page
     // block_table[b * bt_stride + (r >> page_shift)] at row r & (page_size - 1); kc_stride /
     // vc_stride then mean {between pages, between KV heads inside a page, between rows}.

@@ -59,7 +59,7 @@ prefix_valu_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job)
     const int g = blockIdx.z % p.n_kv_heads;
     const int rows_kv = p.group * p.n_tree;  // query rows that share this KV head
 
-    int plen = p.prefix_lens[b];
+    int plen = p.prefix_lens ? p.prefix_lens[b] : p.prefix_len_all;
     plen = plen < 0 ? 0 : (plen > p.max_prefix_len ? p.max_prefix_len : plen);
     const int k_lo = split * plan.split_len;
     int k_hi = k_lo + plan.split_len;

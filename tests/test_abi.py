@@ -219,6 +219,14 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_hybrid_tree_attn(dp, one, one, one, one, one, one, one, one, one, odd, 1 << 40, None) == ls.LS_ERR_WORKSPACE
     bad = good_desc(); bad.n_tree = 0
     assert L.ls_hybrid_tree_attn(ctypes.byref(bad), one, one, one, one, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_SHAPE
+    single = L.ls_hybrid_tree_attn_single
+    assert single(dp, None, one, one, 10, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_NULL
+    assert single(dp, one, one, one, -1, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_SHAPE
+    assert single(dp, one, one, one, 1001, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_SHAPE   # > max_prefix_len
+    assert single(dp, one, one, one, 10, one, one, one, one, one, one, 16, None) == ls.LS_ERR_WORKSPACE
+    two = good_desc(b=2)
+    assert single(ctypes.byref(two), one, one, one, 10, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_SHAPE
+    assert single(None, one, one, one, 10, one, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_NULL
     assert L.ls_cache_attn(dp, one, one, None, one, one, one, one, 1 << 40, None) == ls.LS_ERR_NULL
     assert L.ls_cache_attn(dp, one, one, one, one, one, one, one, 16, None) == ls.LS_ERR_WORKSPACE
     assert L.ls_cache_attn(dp, one, odd, one, one, one, one, one, 1 << 40, None) == ls.LS_ERR_STRIDE

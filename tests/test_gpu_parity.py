@@ -310,6 +310,26 @@ def test_chain_tree_equals_causal_attention_on_device():
     assert err <= 2e-2 * np.abs(ref).max()
 
 
+@pytest.mark.parametrize("name,prefix,used", [("C2", 2000, 2000), ("C2", 2000, 1337), ("C2", 2000, 0), ("C1", 1024, 700),
+                                              ("C4", 1500, 64)])
+def test_single_sequence_form_equals_the_batched_call(name, prefix, used):
+    """ls_hybrid_tree_attn_single takes the prefix length by value; same bits as the device-array form."""
+    batch = small(name, prefix, "peaked")
+    db = DeviceBatch(batch)
+    db.prefix_lens.fill_(used)
+    out_a, lse_a = db.run_full()
+    out_a, lse_a = out_a.clone(), lse_a.clone()
+    out_b, lse_b = torch.full_like(db.out, float("nan")), torch.full_like(db.lse, float("nan"))
+    ls.ls_hybrid_tree_attn_single(db.desc, db.q, db.k_cache, db.v_cache, used, db.k_tree, db.v_tree, db.parents,
+                                  out_b, lse_b, db.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b) and torch.equal(lse_a, lse_b)
+    s = batch.seqs[0]
+    ro, rl = oracle.attn_all(s.q, s.k_cache[:, :used], s.v_cache[:, :used], s.k_tree, s.v_tree, s.parents)
+    say(gates(out_b.float().cpu().numpy()[0], lse_b.cpu().numpy()[0], ro, rl, batch.workload.dtype,
+              f"  single-sequence form {name} prefix {used} of {prefix}", stress=True))
+
+
 def test_repeat_calls_are_bit_identical():
     batch = small("C2", 2500, "peaked")
     db = DeviceBatch(batch)
