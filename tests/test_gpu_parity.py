@@ -527,6 +527,48 @@ def test_full_size_peaked_c3():
     say(gates(got_o, got_l, ro, rl, "bf16", "C3 full size peaked", stress=True))
 
 
+def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
+    """The library keeps no device state of its own: calls on different streams with different
+    workspaces may overlap, and each gives the result it gives alone."""
+    a, b = DeviceBatch(small("C2", 3000, "peaked")), DeviceBatch(small("C4", 2500, "tree"))
+    ref = []
+    for db in (a, b):
+        o, l = db.run_full()
+        torch.cuda.synchronize()
+        ref.append((o.clone(), l.clone()))
+        db.out.fill_(float("nan"))
+        db.lse.fill_(float("nan"))
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(20):
+        a.run_full(stream=s1)
+        b.run_full(stream=s2)
+    torch.cuda.synchronize()
+    for db, (o, l) in zip((a, b), ref):
+        assert torch.equal(db.out, o) and torch.equal(db.lse, l)
+
+
+def test_the_call_neither_allocates_nor_waits():
+    """Device memory in use is the same before and after many calls, and the host is back from a
+    call long before the GPU has finished it (nothing in the call synchronises)."""
+    import time
+    db = DeviceBatch(synth.make_batch(synth.WORKLOADS["C3"], "iid"))
+    db.run_full()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    n = 200
+    t0 = time.perf_counter()
+    for _ in range(n):
+        db.run_full()
+    host = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t0
+    free1, _ = torch.cuda.mem_get_info()
+    assert free1 == free0, "device memory in use changed across calls"
+    say(f"200 calls: host returned after {host * 1e3:.2f} ms, GPU done after {total * 1e3:.2f} ms")
+    assert host < 0.6 * total
+
+
 def test_whole_call_under_hip_graph_capture():
     """The call allocates nothing and records no memset, so it can be captured; every replay
     (with eager calls and synchronisations in between) must reproduce the eager result bit for
