@@ -22,7 +22,8 @@
  * Conventions for every entry point
  *   - Returns LS_OK (0) or a negative ls_status.  No exceptions, no abort.
  *   - Pointers marked DEVICE are device memory owned by the caller; the library
- *     neither allocates nor frees device memory and keeps no device state.
+ *     neither allocates nor frees device memory and keeps no device state (the one
+ *     exception, a fixed scratch array, is described at ls_hybrid_tree_attn_static).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null
  *     stream) and the call returns without synchronising.
  *   - Argument errors are found on the host before anything is launched.  A launch
@@ -158,6 +159,30 @@ int ls_hybrid_tree_attn_single(const ls_desc *desc, const void *q,
                                const void *k_tree, const void *v_tree, const int32_t *parents,
                                void *out, float *lse,
                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * ls_hybrid_tree_attn for callers that cannot allocate device memory or carry a workspace
+ * around: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  It takes no workspace: the split partials, the tree mask and the error words
+ * go to an array of LS_STATIC_SCRATCH_BYTES that is part of the library's code object (every
+ * GPU the library runs on holds one copy from the first use until the process ends).  The
+ * call allocates and frees nothing.  Same kernels, same schedule and bit-identical results
+ * as ls_hybrid_tree_attn.
+ *   - A descriptor whose ls_workspace_bytes() exceeds LS_STATIC_SCRATCH_BYTES is refused with
+ *     LS_ERR_WORKSPACE before anything is launched.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ *     (two streams, two threads) race; the caller must order them.  Nothing in the array has
+ *     to start at zero: every word a call reads was written by that call.
+ *   - The array's address is looked up on the first call on each device (with that device
+ *     current); a HIP error there returns LS_ERR_HIP.
+ *   - The error words of the last call are not reachable through this entry point; validate
+ *     parents on the host (ls_validate_parents_host) or use ls_hybrid_tree_attn.
+ */
+#define LS_STATIC_SCRATCH_BYTES (64u << 20)
+int ls_hybrid_tree_attn_static(const ls_desc *desc, const void *q,
+                               const void *k_cache, const void *v_cache, const int32_t *prefix_lens,
+                               const void *k_tree, const void *v_tree, const int32_t *parents,
+                               void *out, float *lse, void *stream);
 
 /*
  * Unmasked attention of the query rows over the cached keys only, merged over the key

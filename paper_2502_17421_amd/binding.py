@@ -21,6 +21,7 @@ LS_ERR_NULL, LS_ERR_SHAPE, LS_ERR_DTYPE, LS_ERR_STRIDE = -1, -2, -3, -4
 LS_ERR_TREE, LS_ERR_WORKSPACE, LS_ERR_HIP, LS_ERR_UNSUPPORTED = -5, -6, -7, -8
 LS_BF16, LS_F32, LS_F16 = 0, 1, 2
 LS_MAX_TREE = 512
+LS_STATIC_SCRATCH_BYTES = 64 << 20
 
 _i32, _i64, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_float
 _vp, _sz = ctypes.c_void_p, ctypes.c_size_t
@@ -66,6 +67,7 @@ def lib() -> ctypes.CDLL:
     L.ls_workspace_error.argtypes = [dp, _vp, ctypes.POINTER(_vp)]
     L.ls_hybrid_tree_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_hybrid_tree_attn_single.argtypes = [dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.ls_hybrid_tree_attn_static.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
     L.ls_cache_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_build_tree_mask.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
     L.ls_prefix_attn_splitkv.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
@@ -81,6 +83,7 @@ def lib() -> ctypes.CDLL:
     L.ls_kv_commit_paged.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
     for name in ("ls_validate_desc", "ls_validate_parents_host", "ls_prefix_num_splits", "ls_prefix_split_len",
                  "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_hybrid_tree_attn_single",
+                 "ls_hybrid_tree_attn_static",
                  "ls_cache_attn", "ls_build_tree_mask",
                  "ls_prefix_attn_splitkv", "ls_tree_attn_masked", "ls_lse_merge", "ls_tree_accept_greedy",
                  "ls_kv_commit", "ls_hybrid_tree_attn_paged", "ls_cache_attn_paged",
@@ -214,6 +217,17 @@ def ls_hybrid_tree_attn_single(desc, q, k_cache, v_cache, prefix_len, k_tree, v_
                                                                workspace.element_size()), _stream(stream))
     if check:
         _check(st, "ls_hybrid_tree_attn_single")
+    return int(st)
+
+
+def ls_hybrid_tree_attn_static(desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree, parents, out, lse,
+                               stream=None, check: bool = True) -> int:
+    """The whole path without a workspace argument (the library's own fixed scratch array)."""
+    st = lib().ls_hybrid_tree_attn_static(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                          _ptr(prefix_lens), _ptr(k_tree), _ptr(v_tree), _ptr(parents), _ptr(out),
+                                          _ptr(lse), _stream(stream))
+    if check:
+        _check(st, "ls_hybrid_tree_attn_static")
     return int(st)
 
 

@@ -2,8 +2,14 @@
 // workspace layout and kernel dispatch.  No device memory is allocated here.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "ls_internal.hpp"
+
+// Workspace of ls_hybrid_tree_attn_static: one array per GPU, part of the loaded code object and
+// held until the process ends.  In host code the array's name only identifies the symbol; the
+// memory is reached through the per-device address that hipGetSymbolAddress returns.
+static __device__ __align__(256) unsigned char scratch[LS_STATIC_SCRATCH_BYTES];
 
 namespace ls {
 
@@ -114,6 +120,35 @@ Workspace layout(const ls_desc &d, const SplitPlan &plan)
     w.off_o = align_up(w.off_lse + rows * sizeof(float));
     w.total = align_up(w.off_o + rows * d.head_dim * elem_size(d.dtype));
     return w;
+}
+
+}  // namespace
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+
+// Device address of `scratch` on the current device; looked up once per device, with that
+// device current.  Returns nullptr (and leaves *dev_out unset) when HIP reports an error.
+void *static_scratch_of_current_device()
+{
+    static std::mutex lock;
+    static void *ptr_of[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> guard(lock);
+    if (!ptr_of[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(::scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr_of[dev] = ptr;
+    }
+    return ptr_of[dev];
 }
 
 }  // namespace
@@ -434,6 +469,21 @@ int ls_hybrid_tree_attn_single(const ls_desc *desc, const void *q, const void *k
     if (desc->batch != 1 || prefix_len < 0 || prefix_len > desc->max_prefix_len) return LS_ERR_SHAPE;
     return hybrid_contiguous(desc, q, k_cache, v_cache, nullptr, prefix_len, k_tree, v_tree, parents, out, lse,
                              workspace, workspace_bytes, stream);
+}
+
+int ls_hybrid_tree_attn_static(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *prefix_lens, const void *k_tree, const void *v_tree,
+                               const int32_t *parents, void *out, float *lse, void *stream)
+{
+    if (!prefix_lens) return LS_ERR_NULL;
+    const int rc = validate(desc);
+    if (rc) return rc;
+    // the size check comes first: a problem that does not fit is refused whatever the device says
+    if (layout(*desc, plan_call(*desc)).total > (size_t)LS_STATIC_SCRATCH_BYTES) return LS_ERR_WORKSPACE;
+    void *ws = static_scratch_of_current_device();
+    if (!ws) return LS_ERR_HIP;
+    return hybrid_contiguous(desc, q, k_cache, v_cache, prefix_lens, 0, k_tree, v_tree, parents, out, lse, ws,
+                             (size_t)LS_STATIC_SCRATCH_BYTES, stream);
 }
 
 int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
