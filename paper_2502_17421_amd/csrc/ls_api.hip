@@ -154,10 +154,11 @@ void *static_scratch_of_current_device()
 }  // namespace
 
 // Split schedule.  The cached keys of every sequence are cut into pieces of split_len rows
-// (a multiple of 64, the MFMA kernel's key tile); the grid is sized for max_prefix_len.
-// Left to the library, the count S minimises the modelled time of the cached-key kernel:
-// units*S workgroups run in ceil(units*S / CUs) rounds of max_prefix_len / S keys each, plus
-// a small charge per split for the partial results it adds.
+// (a multiple of 64); the grid is sized for max_prefix_len.  Left to the library, the count S
+// minimises the modelled time of the cached-key kernel: units*S workgroups run in
+// ceil(units*S / slots) rounds of max_prefix_len / S keys each (slots: workgroups resident at
+// once, two per compute unit on the MFMA path), plus a small charge per split for the partial
+// results it adds.
 SplitPlan plan_splits(const ls_desc &d, int32_t request)
 {
     constexpr int kTile = 64;
@@ -167,17 +168,17 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
     if (s <= 0) {
         const int group = d.n_q_heads / d.n_kv_heads;
         const int rows_kv = group * d.n_tree;
-        const int rows_wg = is_16bit(d.dtype) ? 256 : 32;
+        const int rows_wg = is_16bit(d.dtype) ? kPrefixRowsPerWorkgroup : 32;
         const int64_t units = (int64_t)d.batch * d.n_kv_heads * ((rows_kv + rows_wg - 1) / rows_wg);
-        const int cus = compute_units();
-        // at least four key tiles per split on the MFMA path; the float path has 32-key tiles
+        const int64_t slots = (int64_t)compute_units() * (is_16bit(d.dtype) ? kPrefixWorkgroupsPerCU : 1);
+        // at least four 64-key pieces per split on the MFMA path; the float path has 32-key tiles
         int64_t s_max = max_p / (is_16bit(d.dtype) ? 4 * kTile : kTile);
         if (s_max > 64) s_max = 64;
         if (s_max < 1) s_max = 1;
         double best = 0.0;
         s = 1;
         for (int64_t cand = 1; cand <= s_max; ++cand) {
-            const int64_t rounds = (units * cand + cus - 1) / cus;
+            const int64_t rounds = (units * cand + slots - 1) / slots;
             const double cost = (double)rounds / (double)cand + 0.0005 * (double)cand;
             if (cand == 1 || cost < best - 1e-12) {
                 best = cost;
@@ -202,63 +203,8 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
     return plan;
 }
 
-// Schedule of the whole-path calls.  On the MFMA path a KV head's query rows go to workgroups
-// of 256; when the last of them holds at most 128 rows (the 68-node tree of the paper under
-// 4:1 grouping gives 256 + 16) its workgroups pass a key tile in about 0.55 of the time of a
-// full one.  If everything fits one round of workgroups anyway, cutting the keys into fewer,
-// longer pieces for that query block and more, shorter ones for the full blocks evens out
-// the finishing times.  With several rounds the hardware's own dispatch order does that.
-SplitPlan plan_call(const ls_desc &d)
-{
-    constexpr int kTile = 64;
-    constexpr double kLightTileTime = 0.55;  // fitted: the best measured pair at 32k keys was 21 / 11 pieces
-    SplitPlan plan = plan_splits(d, 0);
-    if (!is_16bit(d.dtype) || d.max_prefix_len <= 0) return plan;
-    const int rows_kv = d.n_q_heads / d.n_kv_heads * d.n_tree;
-    const int n_qb = (rows_kv + 255) / 256;
-    if (n_qb < 2 || rows_kv - (n_qb - 1) * 256 > 128) return plan;
-    const int64_t units = (int64_t)d.batch * d.n_kv_heads;
-    const int64_t budget = compute_units() / units;  // workgroups per (sequence, KV head) in one round
-    if (units * n_qb * plan.n_splits > compute_units() || budget < n_qb) return plan;
-    const int64_t max_p = d.max_prefix_len;
-    // the search below costs a few microseconds of host time: remember the last shape's answer
-    struct Memo {
-        int32_t key[7];
-        SplitPlan plan;
-    };
-    static thread_local Memo memo = {{0, 0, 0, 0, 0, -1, 0}, {0, 0, 0, 0}};
-    const int32_t key[7] = {d.batch, d.n_q_heads, d.n_kv_heads, d.n_tree, d.max_prefix_len, d.dtype, compute_units()};
-    if (std::memcmp(key, memo.key, sizeof(key)) == 0) return memo.plan;
-    auto remember = [&](const SplitPlan &pl) {
-        std::memcpy(memo.key, key, sizeof(key));
-        memo.plan = pl;
-        return pl;
-    };
-    auto tiles = [&](int64_t s) { return ((max_p + s - 1) / s + kTile - 1) / kTile; };
-    double best = 0.0;
-    int64_t best_f = 0, best_r = 0;
-    for (int64_t sf = 1; sf <= 64; ++sf) {
-        for (int64_t sr = 1; sr <= sf; ++sr) {
-            if ((n_qb - 1) * sf + sr > budget) break;
-            if (tiles(sf) < 4 || tiles(sr) * kTile > kMaxSplitLen) continue;
-            const double t_full = (double)tiles(sf), t_light = kLightTileTime * (double)tiles(sr);
-            const double cost = (t_full > t_light ? t_full : t_light) + 0.03 * (double)sf;
-            if (best_f == 0 || cost < best - 1e-12) {
-                best = cost;
-                best_f = sf;
-                best_r = sr;
-            }
-        }
-    }
-    if (best_f == 0 || best_r == best_f) return remember(plan);
-    auto length = [&](int64_t s) { return (int32_t)(((max_p + s - 1) / s + kTile - 1) / kTile * kTile); };
-    SplitPlan uneven = plan;
-    uneven.split_len = length(best_f);
-    uneven.n_splits = (int32_t)((max_p + uneven.split_len - 1) / uneven.split_len);
-    uneven.rem_split_len = length(best_r);
-    uneven.rem_splits = (int32_t)((max_p + uneven.rem_split_len - 1) / uneven.rem_split_len);
-    return remember(uneven.rem_splits >= uneven.n_splits ? plan : uneven);
-}
+// Schedule of the whole-path calls: the same as the stand-alone cached-key call.
+SplitPlan plan_call(const ls_desc &d) { return plan_splits(d, 0); }
 
 }  // namespace ls
 

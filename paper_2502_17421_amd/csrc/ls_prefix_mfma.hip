@@ -4,15 +4,19 @@
 //
 // Work decomposition.  All G*T query rows that share a KV head (G query heads x T tree
 // tokens) form one dense query tile, so every cached K/V row is fetched from HBM once per
-// KV head and used by all of them.  A workgroup owns (sequence, KV head, key split, block
-// of up to NW*32 query rows); each of its NW waves owns 32 query rows and all keys.  With
-// NW = 8 two waves share a SIMD.  Each wave runs a software pipeline over 32-key steps whose
-// blocks pair the matrix work of the neighbouring steps (output product of step j-1, score
-// product of step j+1) with the softmax arithmetic of step j.
+// KV head.  A workgroup owns (sequence, KV head, key split, block of up to NW*32 query rows);
+// each of its NW waves owns 32 query rows and all keys of the split.  With NW = 8 two waves
+// share a SIMD (256 registers per lane each), so that one wave's matrix instructions overlap
+// the other's vector work; one workgroup per compute unit, so that all of the LDS is one deep
+// ring of key tiles.
 //
 // Data movement.  K and V rows go HBM -> LDS directly (global_load_lds_dwordx4, 16 bytes
-// per lane, no staging registers) into a ring of NS stages of 64 keys each, so several
-// tiles are in flight per compute unit while two are being consumed.  The instruction writes LDS
+// per lane, no staging registers) in tiles of 32 keys.  K tiles and V tiles have rings of
+// their own, because a tile's V rows are read two pipeline steps after its K rows: they are
+// requested one step later than its K rows, and still arrive a step earlier than needed.  With
+// PD requests in flight, issued two at a time (one workgroup barrier per two tiles), the K ring
+// has PD + 3 stages and the V ring PD + 4 (PD = 6: 152 KB at head_dim 128): what a compute unit
+// has in flight is what hides the HBM latency.  The instruction writes LDS
 // linearly (lane l -> base + 16*l), so the bank swizzle is applied on the global side:
 // the lane that fills LDS slot (row, pos) fetches chunk pos ^ swizzle(row) of that row.
 //
@@ -57,6 +61,7 @@
 
 #include "ls_internal.hpp"
 
+
 namespace ls {
 
 namespace {
@@ -69,8 +74,10 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TK = 64;              // keys per LDS stage
-constexpr int SUB = 32;             // keys per softmax step (one MFMA row tile)
+constexpr int TK = 32;              // keys per tile = keys per pipeline step (one MFMA row tile)
+constexpr int PD = 6;               // requests (a K tile and a V tile each) in flight
+constexpr int KS = PD + 3;          // stages of the K ring
+constexpr int VS = PD + 4;          // stages of the V ring
 constexpr float kLazy = 8.f;        // general path: m is raised only when a score exceeds it by 2^8
 // common path: largest row-sum increment taken without raising m; the numerators are stored in
 // the operand type, and a half holds nothing above 65504
@@ -160,8 +167,8 @@ __device__ __forceinline__ int vswz(int row)
 
 }  // namespace
 
-template <int D, int NW, int NS, bool F16>
-__global__ void __launch_bounds__(NW * 64)
+template <int D, int NW, bool F16, bool PAGED>
+__global__ void __launch_bounds__(NW * 64, 2048 / (NW * 64) / 4)  // at most 256 registers per lane: no AGPR copies
 prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, int32_t n_qblocks)
 {
     constexpr int KSTEPS = D / 16;            // contraction steps of S^T = K Q^T
@@ -169,13 +176,17 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     constexpr int CH = D / 8;                 // 16-byte chunks per K/V row
     constexpr int ROWB = D * 2;               // bytes per K/V row
     constexpr int TILEB = TK * ROWB;          // bytes per K (or V) tile
-    constexpr int STAGEB = 2 * TILEB;         // K tile then V tile
     constexpr int ROWS_PER_LOAD = 64 / CH;    // rows one 64-lane load instruction covers
-    constexpr int LOADS = TK / NW / ROWS_PER_LOAD;  // load instructions per wave, tile and tensor
-    static_assert(LOADS >= 1 && TK % (NW * ROWS_PER_LOAD) == 0, "tile rows must divide over the waves");
-    static_assert(NS >= 2 && NS <= 4, "ring depth");
-    constexpr int INFLIGHT = 2 * LOADS;       // vmem instructions per wave and stage
-    static_assert((NS - 1) * INFLIGHT <= 63, "the vmcnt counter holds at most 63 outstanding loads");
+    constexpr int TPT = TK / ROWS_PER_LOAD;   // load instructions per tile and tensor
+    // The first NL waves do all the copying.  With two waves per SIMD these are the older ones,
+    // which the hardware serves first: they reach every barrier early and have the time.
+    constexpr int NL = 4;
+    constexpr int LOADS = TPT / NL;           // load instructions per loader wave, tile and tensor
+    constexpr int INFLIGHT = 2 * LOADS;       // vmem instructions per loader wave and whole request
+    constexpr uint32_t V_RING = KS * TILEB;   // LDS byte offset of the V ring
+    static_assert(LOADS >= 1 && TPT % NL == 0 && NL <= NW, "tile rows must divide over the loader waves");
+    static_assert((PD + 1) * INFLIGHT <= 63, "the vmcnt counter holds at most 63 outstanding loads");
+    static_assert(NW * 32 * ROWB <= (KS + VS) * TILEB, "the partial rows are staged in the rings at the end");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int tid = threadIdx.x;
@@ -188,10 +199,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     // Linear workgroup index: key split fastest, then query block, then (sequence, KV head).
     // Workgroups past that range (one per sequence, present only in the whole-path launch)
     // build the tree mask, which the kernel that follows this one consumes.
-    // Per (sequence, KV head): the full query blocks, n_splits workgroups each, then (if it is cut
-    // differently) the last, light query block with rem_splits workgroups.
-    const int n_qb_even = plan.rem_splits ? n_qblocks - 1 : n_qblocks;
-    const int per_unit = n_qb_even * plan.n_splits + plan.rem_splits;
+    const int per_unit = n_qblocks * plan.n_splits;
     const int n_main = per_unit * p.batch * p.n_kv_heads;
     if ((int)blockIdx.x >= n_main) {
         const int mb = blockIdx.x - n_main;
@@ -203,31 +211,26 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     }
     const int bz = blockIdx.x / per_unit;
     const int in_unit = blockIdx.x % per_unit;
-    const bool light = in_unit >= n_qb_even * plan.n_splits;
-    const int split = light ? in_unit - n_qb_even * plan.n_splits : in_unit % plan.n_splits;
-    const int qblock = light ? n_qb_even : in_unit / plan.n_splits;
-    const int split_len = light ? plan.rem_split_len : plan.split_len;
+    const int split = in_unit % plan.n_splits;
+    const int qblock = in_unit / plan.n_splits;
     const int b = bz / p.n_kv_heads;
     const int g = bz % p.n_kv_heads;
     const int rows_kv = p.group * p.n_tree;
 
     int plen = p.prefix_lens ? p.prefix_lens[b] : p.prefix_len_all;
     plen = plen < 0 ? 0 : (plen > p.max_prefix_len ? p.max_prefix_len : plen);
-    const int k_lo = split * split_len;
-    int k_hi = k_lo + split_len;
+    const int k_lo = split * plan.split_len;
+    int k_hi = k_lo + plan.split_len;
     k_hi = k_hi > plen ? plen : k_hi;
 
     // The query row of this lane.
-    const int m_row = (qblock * NW + wave) * 32 + li;
+    const int wave_row0 = (qblock * NW + wave) * 32;
+    const int m_row = wave_row0 + li;
     const bool q_ok = m_row < rows_kv;
     const int hq = g * p.group + (q_ok ? m_row / p.n_tree : 0);
     const int ti = q_ok ? m_row % p.n_tree : 0;
     const size_t part_row = out.row((size_t)b * p.n_q_heads + hq, split, p.n_tree, ti);
 
-    if (light && split == 0 && lh == 0 && q_ok) {  // the parts this query block does not produce
-        for (int s = plan.rem_splits; s < plan.n_splits; ++s)
-            out.lse[out.row((size_t)b * p.n_q_heads + hq, s, p.n_tree, ti)] = -INFINITY;
-    }
     if (k_lo >= k_hi) {  // empty split: weight zero in the merge
         if (lh == 0 && q_ok) out.lse[part_row] = -INFINITY;
         return;
@@ -250,119 +253,125 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     const int ld_row = lane / CH;  // row within one load instruction
     const int ld_pos = lane % CH;  // LDS chunk position this lane fills
     const uint32_t smem_off = lds_offset(smem);
+    // The rows a loader wave copies: LOADS groups of ROWS_PER_LOAD rows per tensor, group j starting
+    // at tile row load_row0(j).
+    const bool loader = wave < NL;
+    auto load_row0 = [&](int j) __attribute__((always_inline)) { return (wave * LOADS + j) * ROWS_PER_LOAD; };
     // byte offsets of this lane's pieces relative to the first row of a tile (whole tiles)
     uint32_t k_voff[LOADS], v_voff[LOADS];
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
-        const int row = (wave * LOADS + j) * ROWS_PER_LOAD + ld_row;
+        const int row = load_row0(j) + ld_row;
         k_voff[j] = (uint32_t)(row * k_row_bytes) + (ld_pos ^ (row & (CH - 1))) * 16;
         v_voff[j] = (uint32_t)(row * v_row_bytes) + (ld_pos ^ (vswz(row) & (CH - 1))) * 16;
     }
-    // Paged cache: the ids of the pages this split touches, page (first_page + 64 j + l) in lane
-    // l of register j; a tile request then finds its pages with register reads only.
-    const bool paged = p.block_table != nullptr;
+    // Paged cache: the ids of the pages this split touches sit in LDS behind the rings (page
+    // first_page + i at word i); a tile request reads the ones it needs from there.
+    constexpr uint32_t PAGE_TAB = (KS + VS) * TILEB;
     const int page_rows_mask = (1 << p.page_shift) - 1;
     const int first_page = k_lo >> p.page_shift;
-    uint32_t page_tab[kMaxSplitPages / 64] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (paged) {
+    if constexpr (PAGED) {
         const int32_t *tab = p.block_table + (size_t)b * p.bt_stride;
-#pragma unroll
-        for (int j = 0; j < kMaxSplitPages / 64; ++j) {
-            const int idx = first_page + 64 * j + lane;
-            page_tab[j] = idx < p.bt_stride ? (uint32_t)tab[idx] : 0u;
+        for (int i = tid; i < kMaxSplitPages; i += NW * 64) {
+            const int idx = first_page + i;
+            ((uint32_t *)(smem + PAGE_TAB))[i] = idx < p.bt_stride ? (uint32_t)tab[idx] : 0u;
         }
+        __syncthreads();
     }
-    auto page_of = [&](int row) -> int64_t {  // row: wave-uniform cache row of this sequence
+    auto page_of = [&](int row) __attribute__((always_inline)) -> int64_t {  // row: wave-uniform cache row of this sequence
         const int pidx = (row >> p.page_shift) - first_page;
-        const int sel = pidx & 63;
-        uint32_t id = __builtin_amdgcn_readlane(page_tab[0], sel);
-#pragma unroll
-        for (int j = 1; j < kMaxSplitPages / 64; ++j)
-            if ((pidx >> 6) == j) id = __builtin_amdgcn_readlane(page_tab[j], sel);
-        return (int64_t)id;
+        return (int64_t)__builtin_amdgcn_readfirstlane(((const uint32_t *)(smem + PAGE_TAB))[pidx]);
     };
-    // One load instruction covers ROWS_PER_LOAD consecutive rows, which never straddle a page
-    // (page sizes are powers of two >= 16): its base is that of its own page.
-    auto issue_tile_paged = [&](int k0, int stage) {
-        const uint32_t ks_off = __builtin_amdgcn_readfirstlane(smem_off + stage * STAGEB);
+    // Requests.  issue_rows<IS_V>(k0, dst): this wave's LOADS copies of the K (or V) rows of the
+    // tile that starts at cache row k0, to the ring stage at LDS byte offset dst.  Rows past
+    // the end of the split repeat its last row; their scores are masked.
+    // Paged: one load instruction covers ROWS_PER_LOAD consecutive rows, which never straddle a
+    // page (page sizes are powers of two >= 16): its base is that of its own page.
+    auto issue_rows = [&](auto is_v_tag, int k0, uint32_t dst) __attribute__((always_inline)) {
+        constexpr bool IS_V = decltype(is_v_tag)::value;
+        if (!loader) return;  // wave-uniform
+        const uint32_t d0 = __builtin_amdgcn_readfirstlane(smem_off + dst);
         const int last = k_hi - 1 - k0;  // last valid row of the tile (>= TK - 1 for whole tiles)
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const int row0 = (wave * LOADS + j) * ROWS_PER_LOAD;  // wave-uniform
-            // rows past the end of the split repeat its last row, fetched through that row's own group
-            const int last_group = last & ~(ROWS_PER_LOAD - 1);
-            const int src0 = row0 < last_group ? row0 : last_group;
-            const int row = row0 + ld_row;
-            int src = src0 + ld_row;
-            src = src < last ? src : last;
-            const int abs0 = k0 + src0;
-            const int64_t page = page_of(abs0);
-            const int in_page = abs0 & page_rows_mask;
-            const uint8_t *kb = uniform_ptr((const uint8_t *)p.k_cache +
-                                            (page * p.kc_stride[0] + g * p.kc_stride[1] + in_page * p.kc_stride[2]) * 2);
-            const uint8_t *vb = uniform_ptr((const uint8_t *)p.v_cache +
-                                            (page * p.vc_stride[0] + g * p.vc_stride[1] + in_page * p.vc_stride[2]) * 2);
-            const uint32_t ko = (uint32_t)((src - src0) * k_row_bytes) + (ld_pos ^ (row & (CH - 1))) * 16;
-            const uint32_t vo = (uint32_t)((src - src0) * v_row_bytes) + (ld_pos ^ (vswz(row) & (CH - 1))) * 16;
-            copy_to_lds(kb, ko, ks_off + row0 * ROWB);
-            copy_to_lds(vb, vo, ks_off + TILEB + row0 * ROWB);
-        }
-    };
-    auto issue_tile = [&](int k0, int stage) {
-        if (paged) {
-            issue_tile_paged(k0, stage);
-            return;
-        }
-        const uint32_t ks_off = __builtin_amdgcn_readfirstlane(smem_off + stage * STAGEB);
-        const uint8_t *kt_base = uniform_ptr(kbase + k0 * k_row_bytes);
-        const uint8_t *vt_base = uniform_ptr(vbase + k0 * v_row_bytes);
-        if (k0 + TK <= k_hi) {
+        const int64_t row_bytes = IS_V ? v_row_bytes : k_row_bytes;
+        const int64_t *stride = IS_V ? p.vc_stride : p.kc_stride;
+        const uint8_t *tensor = (const uint8_t *)(IS_V ? p.v_cache : p.k_cache);
+        auto swz = [&](int row) __attribute__((always_inline)) { return (IS_V ? vswz(row) : row) & (CH - 1); };
+        if constexpr (PAGED) {
 #pragma unroll
             for (int j = 0; j < LOADS; ++j) {
-                const int row0 = (wave * LOADS + j) * ROWS_PER_LOAD;  // wave-uniform
-                copy_to_lds(kt_base, k_voff[j], ks_off + row0 * ROWB);
-                copy_to_lds(vt_base, v_voff[j], ks_off + TILEB + row0 * ROWB);
+                const int row0 = load_row0(j);  // wave-uniform
+                // rows past the end repeat the last row, fetched through that row's own group
+                const int last_group = last & ~(ROWS_PER_LOAD - 1);
+                const int src0 = row0 < last_group ? row0 : last_group;
+                const int row = row0 + ld_row;
+                int src = src0 + ld_row;
+                src = src < last ? src : last;
+                const int abs0 = k0 + src0;
+                const int64_t page = page_of(abs0);
+                const int in_page = abs0 & page_rows_mask;
+                const uint8_t *base = uniform_ptr(tensor + (page * stride[0] + g * stride[1] + in_page * stride[2]) * 2);
+                copy_to_lds(base, (uint32_t)((src - src0) * row_bytes) + (ld_pos ^ swz(row)) * 16, d0 + row0 * ROWB);
             }
         } else {
-            // ragged last tile: rows past the end repeat the last valid row; their scores are masked
+            const uint8_t *base = uniform_ptr((IS_V ? vbase : kbase) + k0 * row_bytes);
+            if (last >= TK - 1) {
 #pragma unroll
-            for (int j = 0; j < LOADS; ++j) {
-                const int row0 = (wave * LOADS + j) * ROWS_PER_LOAD;
-                const int row = row0 + ld_row;
-                const int last = k_hi - 1 - k0;
-                const int src = row < last ? row : last;
-                const uint32_t ko = (uint32_t)(src * k_row_bytes) + (ld_pos ^ (row & (CH - 1))) * 16;
-                const uint32_t vo = (uint32_t)(src * v_row_bytes) + (ld_pos ^ (vswz(row) & (CH - 1))) * 16;
-                copy_to_lds(kt_base, ko, ks_off + row0 * ROWB);
-                copy_to_lds(vt_base, vo, ks_off + TILEB + row0 * ROWB);
+                for (int j = 0; j < LOADS; ++j)
+                    copy_to_lds(base, IS_V ? v_voff[j] : k_voff[j], d0 + load_row0(j) * ROWB);
+            } else {
+#pragma unroll
+                for (int j = 0; j < LOADS; ++j) {
+                    const int row0 = load_row0(j);
+                    const int row = row0 + ld_row;
+                    const int src = row < last ? row : last;
+                    copy_to_lds(base, (uint32_t)(src * row_bytes) + (ld_pos ^ swz(row)) * 16, d0 + row0 * ROWB);
+                }
             }
         }
     };
 
-    // Tiles requested ahead of the one being consumed: the V half of a tile is still read one
-    // step after its keys were scored (see the pipeline below), so of the NS stages one holds
-    // that tile, one the current tile and PD = NS - 2 are in flight.
-    constexpr int PD = NS - 2;
-    static_assert(PD >= 1 && PD <= 2, "prefetch distance");
     const int n_tiles = (k_hi - k_lo + TK - 1) / TK;
-    const int n_prologue = n_tiles < PD ? n_tiles : PD;
     // Tile order: the softmax does not care in which order keys arrive, so split s starts at
     // its tile (s mod n_tiles) and wraps around.  All workgroups start together; with every
     // split reading from its first row their addresses would differ by multiples of the split
     // size only and crowd a few memory channels.
-    const int rot = split % n_tiles;
-    auto tile_k0 = [&](int t) {
-        int tt = t + rot;
-        tt = tt >= n_tiles ? tt - n_tiles : tt;
-        return k_lo + tt * TK;
+    const int key_first = k_lo + (split % n_tiles) * TK;  // first key of tile 0
+    const int key_wrap = k_lo + n_tiles * TK;
+    auto next_key0 = [&](int k0) __attribute__((always_inline)) { return k0 + TK == key_wrap ? k_lo : k0 + TK; };
+    auto next_k = [&](uint32_t off) __attribute__((always_inline)) { return off + TILEB == KS * TILEB ? 0u : off + TILEB; };
+    auto next_v = [&](uint32_t off) __attribute__((always_inline)) {
+        return off + TILEB == V_RING + VS * TILEB ? V_RING : off + TILEB;
     };
+    using is_k = std::integral_constant<bool, false>;
+    using is_v = std::integral_constant<bool, true>;
+    // Requests, in tile order: request r (r >= -(PD+1)) is the K rows of tile r+PD+1 and the V rows
+    // of tile r+PD, as far as these tiles exist; a request with both parts is INFLIGHT load
+    // instructions per wave.  The state below is that of the next request.
+    int rq_kt = 0, rq_k0 = key_first, rq_vt = 0, rq_v0 = key_first;
+    uint32_t rq_koff = 0, rq_voff = V_RING;
+    auto request_k = [&]() __attribute__((always_inline)) {
+        if (rq_kt < n_tiles) issue_rows(is_k{}, rq_k0, rq_koff);
+        ++rq_kt;
+        rq_k0 = next_key0(rq_k0);
+        rq_koff = next_k(rq_koff);
+    };
+    auto request_v = [&]() __attribute__((always_inline)) {
+        if (rq_vt < n_tiles) issue_rows(is_v{}, rq_v0, rq_voff);
+        ++rq_vt;
+        rq_v0 = next_key0(rq_v0);
+        rq_voff = next_v(rq_voff);
+    };
+    request_k();  // request -(PD+1)
 #pragma unroll
-    for (int s = 0; s < PD; ++s)
-        if (s < n_prologue) issue_tile(tile_k0(s), s);
+    for (int r = -PD; r < 0; ++r) {
+        request_k();
+        request_v();
+    }
 
-    // collect Q: everything older than the prologue tiles has landed
-    if (PD >= 2 && n_prologue == 2) wait_vmem<(PD >= 2 ? 2 : 1) * INFLIGHT>();
-    else wait_vmem<INFLIGHT>();
+    // Collect Q and the K rows of tile 0: everything older than requests -PD .. -1 has landed.
+    // (A wave that copies nothing has only its Q loads outstanding.)
+    if (loader && n_tiles > PD) wait_vmem<PD * INFLIGHT>();
+    else wait_vmem<0>();  // short split: its requests are not all whole; wait for everything
     bf16x8 q_reg[KSTEPS];
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
@@ -375,93 +384,53 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[mt][r] = 0.f;
+        for (int e = 0; e < 16; ++e) o_acc[mt][e] = 0.f;
     float m_run = -INFINITY;  // reference exponent in raw-score units (see the header comment)
     float l_run = 0.f;        // sum of the numerators over this lane's keys only
     const float c = p.scale_log2;
 
-    // per-lane LDS offsets of the operand reads
-    const int k_lane_off = li * ROWB;              // + 32*kt rows; chunk (2kk+lh) ^ (li & (CH-1))
-    const int k_swz = li & (CH - 1);
+    // Per-lane LDS addresses of the operand reads for a tile at ring offset 0 (the base of the
+    // dynamic LDS is a multiple of 256 and is included).
+    // K fragment kk: row li, chunk (2 kk + lh) under the row's swizzle, i.e. at chunk position
+    // (2 kk + lh) ^ (li & (CH-1)); the chunk field of the offset is therefore k_off0 ^ (kk << 5).
+    // V fragments alike: d tile mt moves the chunk position by mt << 2, i.e. v_off0 ^ (mt << 6).
+    const uint32_t k_off0 = smem_off + li * ROWB + ((lh ^ (li & (CH - 1))) * 16);
     const int tr_s = lane & 15;                    // lane within its 16-lane transpose block
     const int tr_row = 4 * lh + (tr_s >> 2);       // key row (within a 16-key step) this lane addresses
     const int tr_dchunk = 2 * ((lane >> 4) & 1) + ((tr_s & 3) >> 1);  // 16-byte chunk within a 32-wide d tile
     const int tr_sub = (tr_s & 1) * 8;             // byte offset inside the chunk
     const int tr_swz = vswz(tr_row) & (CH - 1);    // rows +8, +16, ... keep row & 3
-    int v_lane_off[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-        v_lane_off[mt] = tr_row * ROWB + (((4 * mt + tr_dchunk) ^ tr_swz) * 16) + tr_sub;
+    const uint32_t v_off0 = smem_off + tr_row * ROWB + ((tr_dchunk ^ tr_swz) * 16) + tr_sub;
 
     // ---- building blocks of the pipeline -----------------------------------------------------
-    auto wait_tile = [&](int t) {  // this wave's copies of tile t have landed
-        const int younger = n_tiles - 1 - t < PD - 1 ? n_tiles - 1 - t : PD - 1;
-        if (PD >= 2 && younger >= 1) wait_vmem<(PD >= 2 ? 1 : 0) * INFLIGHT>();
-        else wait_vmem<0>();
-    };
-    auto fetch_k = [&](const uint8_t *ktile, int kt, bf16x8 (&kf)[KSTEPS]) {
+    // Workgroup barrier of the key loop, without the compiler's wait for outstanding LDS reads:
+    // the stages that are written after it were last read at least a half-step before it, by
+    // matrix instructions that have been issued, so those reads are complete; the reads still
+    // outstanding are fragment prefetches from other stages.
+    auto ring_barrier = [&]() __attribute__((always_inline)) { asm volatile("s_barrier" ::: "memory"); };
+    auto mask_tail = [&](floatx16 &s_acc, int key0) __attribute__((always_inline)) {  // keys past the end of the split weigh nothing
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            const int pos = (2 * kk + lh) ^ k_swz;
-            kf[kk] = __builtin_bit_cast(bf16x8, *(const uint4 *)(ktile + kt * SUB * ROWB + k_lane_off + pos * 16));
+        for (int e = 0; e < 16; ++e) {
+            const int key = key0 + 8 * (e >> 2) + 4 * lh + (e & 3);
+            if (key >= k_hi) s_acc[e] = -INFINITY;
         }
     };
-    auto fetch_v = [&](const uint8_t *vtile, int kt, bf16x8 (&vf)[2][MT]) {
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const uint8_t *vp = vtile + (kt * SUB + a * 16) * ROWB + v_lane_off[mt];
-                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp));
-                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4 *)LS_LDS(vp + 8 * ROWB));
-                const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
-                vf[a][mt] = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
-            }
-    };
-    auto score = [&](const bf16x8 (&kf)[KSTEPS]) {  // S^T = K Q^T for 32 keys
-        floatx16 s_acc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) s_acc = mfma32<F16>(kf[kk], q_reg[kk], s_acc);
-        return s_acc;
-    };
-    auto second_product = [&](const bf16x8 (&vf)[2][MT], const uint32_t (&pp)[8]) {  // O^T += V^T P^T
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            const bf16x8 pb =
-                __builtin_bit_cast(bf16x8, make_uint4(pp[4 * a], pp[4 * a + 1], pp[4 * a + 2], pp[4 * a + 3]));
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) o_acc[mt] = mfma32<F16>(vf[a][mt], pb, o_acc[mt]);
-        }
-    };
-    auto mask_tail = [&](floatx16 &s_acc, int key0) {  // keys past the end of the split weigh nothing
-        if (key0 + SUB > k_hi) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = key0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (key >= k_hi) s_acc[r] = -INFINITY;
-            }
-        }
-    };
-    auto numerators = [&](const floatx16 &s_acc, uint32_t (&pp)[8]) {  // with the current m_run
+    auto numerators = [&](const floatx16 &s_acc, uint32_t (&pp)[8]) __attribute__((always_inline)) {  // with the current m_run
         const float mc = m_run == -INFINITY ? 0.f : m_run * c;
         float sum = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(s_acc[r] * c - mc);
-            const float p1 = __builtin_amdgcn_exp2f(s_acc[r + 1] * c - mc);
-            pp[r >> 1] = pack_numerators<F16>(p0, p1);
+        for (int e = 0; e < 16; e += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(s_acc[e] * c - mc);
+            const float p1 = __builtin_amdgcn_exp2f(s_acc[e + 1] * c - mc);
+            pp[e >> 1] = pack_numerators<F16>(p0, p1);
             sum += p0 + p1;
         }
         return sum;
     };
-    auto raise_reference = [&](const floatx16 &s_acc) {  // general path: lift m_run, rescale O and l
+    auto raise_reference = [&](const floatx16 &s_acc) __attribute__((always_inline)) {  // general path: lift m_run, rescale O and l
         float mx = s_acc[0];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_acc[r]);
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_acc[e]);
         mx = half_max(mx);
         const bool grow = (mx - m_run) * c > kLazy;  // also true while m_run is -inf
         if (__any(grow)) {
@@ -473,120 +442,226 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o_acc[mt][r] *= alpha;
+                for (int e = 0; e < 16; ++e) o_acc[mt][e] *= alpha;
         }
     };
 
-    // ---- software pipeline over 32-key steps --------------------------------------------------
-    // Step j scores keys, turns scores into numerators and adds their weighted values to O.
-    // One pipeline block handles three independent pieces of neighbouring steps: the output
-    // product of step j-1 (matrix core), the softmax arithmetic of step j (vector ALU) and the
-    // score product of step j+1 (matrix core).  Every block thus carries 16 matrix instructions
-    // next to its vector work, for this wave and for the one sharing its SIMD alike.
-    bf16x8 k_frag[KSTEPS];
-    bf16x8 v_frag[2][MT];
-    uint32_t p_prev[8];
-    floatx16 s_cur;
+    // ---- software pipeline ---------------------------------------------------------------------
+    // A step is one tile: 32 keys against the wave's 32 queries: a score product (KSTEPS matrix
+    // instructions), the softmax arithmetic (16 scores per lane) and an output product (KSTEPS
+    // matrix instructions).  Three steps are in flight, in two register slots that alternate
+    // (even steps slot 0, odd steps slot 1): half-step h issues the score product of step h into
+    // its slot X and the output product of step h-2 from the same slot, one matrix instruction
+    // at a time, and between them the softmax arithmetic of step h-1 in the other slot.  So
+    // every matrix instruction is followed by independent vector work.
+    // K and V fragments rotate through FS register slots each: fragment i sits in slot i % FS and
+    // is replaced, right after the matrix instruction that reads it, by fragment i + FS (of the
+    // same tile, or of the next half-step's tile), FS matrix-instruction pairs before its use.
+    // Scheduling barriers pin this order: left to itself the compiler hoists the LDS reads and
+    // runs out of registers.
+    constexpr int FS = KSTEPS / 2;
+    bf16x8 k_frag[FS];
+    bf16x8 v_frag[FS];
+    floatx16 s_sl[2];
+    uint32_t p_sl[2][8];
+    float mc = 0.f;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int f = 0; f < FS; ++f) v_frag[f] = k_frag[f] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) v_frag[a][mt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int r = 0; r < 8; ++r) p_prev[r] = 0;  // the first block's output product adds zero
+        for (int e = 0; e < 8; ++e) p_sl[x][e] = 0;  // an output product of zeros adds nothing
 
-    wait_tile(0);
-    __syncthreads();
-    if (PD < n_tiles) issue_tile(tile_k0(PD), PD % NS);
-    // A wave whose 32 rows all lie past the last query row of the KV head (the last query block
-    // of a head whose row count is not a multiple of the block) only keeps feeding the ring:
-    // its share of every tile, and every barrier of the loop below.
-    if ((qblock * NW + wave) * 32 >= rows_kv) {
-        for (int t = 0; t + 1 < n_tiles; ++t) {
-            wait_tile(t + 1);
-            __syncthreads();
-            if (t + 1 + PD < n_tiles) issue_tile(tile_k0(t + 1 + PD), (t + 1 + PD) % NS);
-        }
-        return;
-    }
-    fetch_k(smem, 0, k_frag);
-    s_cur = score(k_frag);
-    mask_tail(s_cur, tile_k0(0));
-    raise_reference(s_cur);  // sets m_run from the first 32 keys (at least one of them is valid)
-
-    // one block: consumes s_cur / p_prev / v_frag, leaves the next step's in their place
-    auto block = [&](auto has_next_tag, const uint8_t *k_next, int kt_next, const uint8_t *v_cur, int kt_cur,
-                     int key0_next) {
-        constexpr bool has_next = decltype(has_next_tag)::value;
-        if constexpr (has_next) fetch_k(k_next, kt_next, k_frag);
-        uint32_t p_cur[8];
-        floatx16 s_next = s_cur;
-        if constexpr (has_next) {
-            // output-product and score MFMAs alternate, so that no matrix instruction depends on
-            // the one issued just before it
-            bf16x8 pb[2];
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-                pb[a] = __builtin_bit_cast(bf16x8, make_uint4(p_prev[4 * a], p_prev[4 * a + 1], p_prev[4 * a + 2],
-                                                              p_prev[4 * a + 3]));
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
-#pragma unroll
-            for (int i = 0; i < KSTEPS; ++i) {
-                o_acc[i % MT] = mfma32<F16>(v_frag[i / MT][i % MT], pb[i / MT], o_acc[i % MT]);
-                s_next = mfma32<F16>(k_frag[i], q_reg[i], s_next);
-            }
-        } else {
-            second_product(v_frag, p_prev);
-        }
-        float sum = numerators(s_cur, p_cur);
-        fetch_v(v_cur, kt_cur, v_frag);
-        if (__any(!(sum < kSumCap<F16>))) {  // also catches inf and nan: redo this step on the general path
-            raise_reference(s_cur);
-            sum = numerators(s_cur, p_cur);
-        }
-        l_run += sum;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) p_prev[r] = p_cur[r];
-        if constexpr (has_next) mask_tail(s_next, key0_next);
-        s_cur = s_next;
-    };
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
+    constexpr int PPG = 8 / KSTEPS;  // score pairs of the softmax per pair of matrix instructions
 
-    for (int t = 0; t + 1 < n_tiles; ++t) {
-        const uint8_t *ks = smem + (t % NS) * STAGEB;
-        const uint8_t *vs = ks + TILEB;
-        const int k0 = tile_k0(t);
-        // first half of tile t: the next step is the second half of the same tile
-        block(yes{}, ks, 1, vs, 0, k0 + SUB);
-        // second half: the next step opens tile t+1, which needs the barrier
-        wait_tile(t + 1);
-        __syncthreads();  // tile t+1 is complete in LDS; nobody reads tile t-1 any more
-        if (t + 1 + PD < n_tiles) issue_tile(tile_k0(t + 1 + PD), (t + 1 + PD) % NS);
-        block(yes{}, smem + ((t + 1) % NS) * STAGEB, 0, vs, 1, tile_k0(t + 1));
+    // fragment f (0 .. KSTEPS-1) of the K tile / V tile whose per-lane base is k_base / v_base
+    // k_base / v_base: LDS ADDRESS (ring base included) of the lane's piece of fragment 0; fragment f
+    // differs in the chunk field only, which one XOR reaches (all other terms are multiples of 256).
+    typedef __attribute__((address_space(3))) const uint4 *lds_u4;
+    typedef __attribute__((address_space(3))) shortx4 *lds_s4;
+    auto read_k = [&](uint32_t k_base, int f) __attribute__((always_inline)) {
+        return __builtin_bit_cast(bf16x8, *(lds_u4)(uintptr_t)(k_base ^ (uint32_t)(f << 5)));
+    };
+    auto read_v = [&](uint32_t v_base, int f) __attribute__((always_inline)) {  // f = 16-key half * MT + d tile
+        const uint32_t a = (v_base ^ (uint32_t)((f % MT) << 6)) + ((f / MT) * 16) * ROWB;
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)a);
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(uintptr_t)(a + 8 * ROWB));
+        const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+        return __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
+    };
+
+    // Half-step of slot X.  QK: score product of the tile at LDS offset k_cur into s_sl[X].
+    // SM: softmax of s_sl[1-X] into p_sl[1-X].  The output product of p_sl[X] with the V tile at
+    // v_cur always runs.  KN / VN: the next half-step has a score product (of the tile at k_next) /
+    // an output product (with the tile at v_next), whose first fragments are requested here.
+    auto half_step = [&](auto x_tag, auto qk_tag, auto sm_tag, auto kn_tag, auto vn_tag, uint32_t k_cur,
+                         uint32_t k_next, uint32_t v_cur, uint32_t v_next) __attribute__((always_inline)) {
+        constexpr int X = decltype(x_tag)::value, Y = 1 - X;
+        constexpr bool QK = decltype(qk_tag)::value, SM = decltype(sm_tag)::value;
+        constexpr bool KN = decltype(kn_tag)::value, VN = decltype(vn_tag)::value;
+        bf16x8 pb[2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+            pb[a] = __builtin_bit_cast(bf16x8, make_uint4(p_sl[X][4 * a], p_sl[X][4 * a + 1], p_sl[X][4 * a + 2],
+                                                          p_sl[X][4 * a + 3]));
+        const float neg_mc = -mc;
+        // tile offsets are multiples of 256, so adding them leaves the chunk field alone
+        const uint32_t kc = k_cur + k_off0, kn = k_next + k_off0, vc = v_cur + v_off0, vn = v_next + v_off0;
+        float sum = 0.f;
+        floatx16 s_new;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s_new[e] = 0.f;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < KSTEPS; ++i) {
+            float pe[PPG][2];
+            o_acc[i % MT] = mfma32<F16>(v_frag[i % FS], pb[i / MT], o_acc[i % MT]);
+            __builtin_amdgcn_sched_barrier(0);  // the V fragment is dead from here on: replace it
+            if constexpr (SM) {
+#pragma unroll
+                for (int u = 0; u < PPG; ++u) {
+                    const int e = 2 * (i * PPG + u);
+                    pe[u][0] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_sl[Y][e], c, neg_mc));
+                    pe[u][1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_sl[Y][e + 1], c, neg_mc));
+                }
+            }
+            if (i < FS) v_frag[i % FS] = read_v(vc, i + FS);
+            else if constexpr (VN) v_frag[i % FS] = read_v(vn, i - FS);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (QK) s_new = mfma32<F16>(k_frag[i % FS], q_reg[i], s_new);
+            __builtin_amdgcn_sched_barrier(0);  // the K fragment is dead from here on: replace it
+            if constexpr (SM) {
+#pragma unroll
+                for (int u = 0; u < PPG; ++u) {
+                    p_sl[Y][i * PPG + u] = pack_numerators<F16>(pe[u][0], pe[u][1]);
+                    sum += pe[u][0] + pe[u][1];
+                    // keeps the pack and the adds here (they would be sunk below the loop, and the
+                    // numerators would stay live in fp32 until then)
+                    asm volatile("" : "+v"(p_sl[Y][i * PPG + u]), "+v"(sum));
+                }
+            }
+            if (i < FS) {
+                if constexpr (QK) k_frag[i % FS] = read_k(kc, i + FS);
+            } else if constexpr (KN) {
+                k_frag[i % FS] = read_k(kn, i - FS);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (QK) s_sl[X] = s_new;
+        if constexpr (SM) {
+            if (__any(!(sum < kSumCap<F16>))) {  // also catches inf and nan: redo this step on the general path
+                raise_reference(s_sl[Y]);
+                sum = numerators(s_sl[Y], p_sl[Y]);
+                mc = m_run * c;
+            }
+            l_run += sum;
+        }
+    };
+    using X0 = std::integral_constant<int, 0>;
+    using X1 = std::integral_constant<int, 1>;
+
+    __syncthreads();  // the K rows of tile 0 are complete in LDS
+    // Before half-step 1 (which reads K rows of tile 1): request -PD has landed, for this wave and
+    // then for everybody; request 0 follows.
+    auto advance0 = [&]() __attribute__((always_inline)) {
+        if (n_tiles > 1) {
+            if (n_tiles > PD) wait_vmem<(PD - 1) * INFLIGHT>();
+            else wait_vmem<0>();
+            ring_barrier();
+            request_k();
+            request_v();
+        }
+    };
+    // Before half-steps h and h+1 (h odd), which read K rows up to tile h+2: requests up to h+1-PD
+    // have landed; requests h and h+1 follow, into stages last read in half-step h-1 or earlier.
+    // Near the end of the split the outstanding requests are not whole any more, and the wave
+    // waits for everything.
+    auto advance_pair = [&](int h) __attribute__((always_inline)) {
+        if (h + PD < n_tiles) wait_vmem<(PD - 2) * INFLIGHT>();
+        else wait_vmem<0>();
+        ring_barrier();
+        request_k();
+        request_v();
+        request_k();
+        request_v();
+    };
+    // A wave whose rows all lie past the last query row of the KV head (the last query block of a
+    // head whose row count is not a multiple of the block) only keeps feeding the rings: its
+    // share of every tile, and every barrier of the code below.
+    if (wave_row0 >= rows_kv) {
+        advance0();
+        for (int h = 1; h + 1 < n_tiles; h += 2) advance_pair(h);
+        __syncthreads();
+        return;
     }
-    {  // the last tile: its second half has no successor
-        const int t = n_tiles - 1;
-        const uint8_t *ks = smem + (t % NS) * STAGEB;
-        const uint8_t *vs = ks + TILEB;
-        block(yes{}, ks, 1, vs, 0, tile_k0(t) + SUB);
-        block(no{}, ks, 0, vs, 1, 0);
+
+    // scores of step 0 and the reference exponent
+    {
+        bf16x8 k0f[KSTEPS];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) k0f[kk] = read_k(k_off0, kk);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s_sl[0][e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) s_sl[0] = mfma32<F16>(k0f[kk], q_reg[kk], s_sl[0]);
     }
-    second_product(v_frag, p_prev);  // the output product of the last step
+    if (key_first + TK > k_hi) mask_tail(s_sl[0], key_first);
+    raise_reference(s_sl[0]);  // sets m_run from the first 32 keys (at least one of them is valid)
+    mc = m_run * c;
+    advance0();
+    if (n_tiles > 1) {
+#pragma unroll
+        for (int f = 0; f < FS; ++f) k_frag[f] = read_k(TILEB + k_off0, f);
+    }
+
+    // Half-step h: scores of step h; output of step h-2; softmax of step h-1.  Steps -1 and -2 do
+    // not exist: their numerators are zeros, and the "V tile" they are multiplied with is the K
+    // tile in ring stage 0 (any finite data gives zero; rows past the end of a split repeat valid
+    // rows).  After the last step there is no next K tile: the reads requested for it return
+    // whatever the stage holds, and nothing uses them.  A split with an odd number of tiles ends
+    // on a step that does not exist either: all its scores are masked.
+    // LDS offsets of K(h), K(h+1), V(h-2), V(h-1), and the first key of tile h:
+    uint32_t k_cur = TILEB, k_nxt = 2 * TILEB, v_cur = 0, v_nxt = V_RING;
+    int key_h = next_key0(key_first);
+    auto step_on = [&]() __attribute__((always_inline)) {
+        k_cur = k_nxt;
+        k_nxt = next_k(k_nxt);
+        v_cur = v_nxt;
+        v_nxt = next_v(v_nxt);
+        key_h = next_key0(key_h);
+    };
+    int h = 1;
+    for (; h + 1 < n_tiles; h += 2) {
+        advance_pair(h);
+        half_step(X1{}, yes{}, yes{}, yes{}, yes{}, k_cur, k_nxt, v_cur, v_nxt);
+        if (key_h + TK > k_hi) mask_tail(s_sl[1], key_h);
+        step_on();
+        half_step(X0{}, yes{}, yes{}, yes{}, yes{}, k_cur, k_nxt, v_cur, v_nxt);
+        if (key_h + TK > k_hi) mask_tail(s_sl[0], key_h);
+        step_on();
+    }
+    // h = n_tiles - 1 (one step left to score) or h = n_tiles (none: the step scored here is void)
+    if (h >= n_tiles) key_h = k_hi;
+    half_step(X1{}, yes{}, yes{}, no{}, yes{}, h < n_tiles ? k_cur : 0u, 0, v_cur, v_nxt);
+    if (key_h + TK > k_hi) mask_tail(s_sl[1], key_h);
+    step_on();
+    if (h >= n_tiles) v_nxt = 0;  // V of the void step: any finite data
+    half_step(X0{}, no{}, yes{}, no{}, yes{}, 0, 0, v_cur, v_nxt);  // output h-1; softmax h
+    step_on();
+    half_step(X1{}, no{}, no{}, no{}, no{}, 0, 0, v_cur, 0);       // output h
 
     // ---- epilogue: normalise and store this split's partial result -----------------------
+    __syncthreads();  // every wave is done reading tiles: the rings are free
     const float l_tot = half_sum(l_run);
     const float inv = 1.f / l_tot;
     if (out.o_is_16bit) {
         // A lane holds 4-element runs of one query row, 256 bytes apart from its neighbours':
         // stored as they are, every store instruction would touch 32 rows with 16 bytes each.
-        // The rows go through LDS instead and leave as whole rows, 16 bytes per lane.  The
-        // two ring stages after the last tile's are free: no tile was requested into them any
-        // more, and every wave has passed the barrier after which their old tiles were dead.
-        // Each wave owns a quarter of a stage, so no barrier is needed.
-        const int t_last = n_tiles - 1;
-        uint8_t *mine = smem + ((t_last + 1 + wave / 4) % NS) * STAGEB + (wave % 4) * (32 * ROWB);
-        static_assert(STAGEB == 4 * 32 * ROWB && NW <= 8 && NS >= 4, "four waves stage their rows in one ring stage");
+        // The rows go through LDS instead (each wave its own 32 rows, so no further barrier)
+        // and leave as whole rows, 16 bytes per lane.
+        uint8_t *mine = smem + wave * (32 * ROWB);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -597,16 +672,16 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
                 const int chunk = (4 * mt + rg) ^ (li & (CH - 1));
                 *(uint2 *)(mine + li * ROWB + chunk * 16 + lh * 8) = v;
             }
-        // the row index and validity of query row r live in lane r
+        // the row index and validity of query row j live in lane j
         const uint32_t my_row = (uint32_t)part_row;
         constexpr int ROWS_PER_STORE = 64 / CH;
 #pragma unroll
         for (int j = 0; j < 32 / ROWS_PER_STORE; ++j) {
-            const int r = j * ROWS_PER_STORE + lane / CH;
+            const int row = j * ROWS_PER_STORE + lane / CH;
             const int cpos = lane % CH;
-            const uint4 v = *(const uint4 *)(mine + r * ROWB + ((cpos ^ (r & (CH - 1))) * 16));
-            const uint32_t prow = __shfl(my_row, r);
-            const int ok = __shfl((int)q_ok, r);
+            const uint4 v = *(const uint4 *)(mine + row * ROWB + ((cpos ^ (row & (CH - 1))) * 16));
+            const uint32_t prow = __shfl(my_row, row);
+            const int ok = __shfl((int)q_ok, row);
             // streaming stores: whole rows that nobody on this compute unit reads again; they leave
             // the L2 as they are written instead of in one burst when the kernel ends
             if (ok)
@@ -636,28 +711,25 @@ bool prefix_mfma_supports(const Problem &p, int dtype)
 {
     // the tile loads address rows of one tile with 32-bit byte offsets
     const int64_t max_row_bytes = 2 * (p.kc_stride[2] > p.vc_stride[2] ? p.kc_stride[2] : p.vc_stride[2]);
-    return is_16bit(dtype) && (p.head_dim == 128 || p.head_dim == 64) && max_row_bytes * TK < (1ll << 31);
+    return is_16bit(dtype) && (p.head_dim == 128 || p.head_dim == 64) && max_row_bytes * 64 < (1ll << 31);
 }
 
 namespace {
 
-template <int D, int NW, int NS, bool F16>
+template <int D, int NW, bool F16, bool PAGED>
 hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
                       hipStream_t stream)
 {
-    constexpr int lds_bytes = NS * 2 * TK * D * 2;
-    static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a compute unit");
-    auto kernel = prefix_mfma_kernel<D, NW, NS, F16>;
+    constexpr int lds_bytes = (KS + VS) * TK * D * 2 + (PAGED ? kMaxSplitPages * 4 : 0);
+    static_assert(lds_bytes <= 160 * 1024, "the rings exceed the 160 KB of a compute unit");
+    auto kernel = prefix_mfma_kernel<D, NW, F16, PAGED>;
     static hipError_t attr = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  lds_bytes);
     if (attr != hipSuccess) return attr;
     const int rows_kv = p.group * p.n_tree;
-    const int rows_wg = NW * 32;
-    const int n_qblocks = (rows_kv + rows_wg - 1) / rows_wg;
-    if (plan.rem_splits < 0 || plan.rem_splits > plan.n_splits || (plan.rem_splits && n_qblocks < 2))
-        return hipErrorInvalidValue;
-    const int64_t per_unit = (int64_t)plan.n_splits * (plan.rem_splits ? n_qblocks - 1 : n_qblocks) + plan.rem_splits;
-    const int64_t n_main = per_unit * p.batch * p.n_kv_heads;
+    const int n_qblocks = (rows_kv + NW * 32 - 1) / (NW * 32);
+    if (plan.rem_splits != 0) return hipErrorInvalidValue;
+    const int64_t n_main = (int64_t)plan.n_splits * n_qblocks * p.batch * p.n_kv_heads;
     const int64_t n_blocks = n_main + (mask_job.parents ? p.batch : 0);
     if (n_blocks > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), lds_bytes, stream, p, plan, out, mask_job,
@@ -672,12 +744,19 @@ hipError_t launch_prefix_mfma(const Problem &p, int dtype, const SplitPlan &plan
 {
     const int rows_kv = p.group * p.n_tree;
     const bool f16 = dtype == LS_F16;
-#define LS_MFMA_CASE(DD, WW)                                                              \
-    (f16 ? launch_one<DD, WW, 4, true>(p, plan, out, mask_job, stream)                   \
-         : launch_one<DD, WW, 4, false>(p, plan, out, mask_job, stream))
-    if (p.head_dim == 128) return rows_kv > 128 ? LS_MFMA_CASE(128, 8) : LS_MFMA_CASE(128, 4);
-    if (p.head_dim == 64) return rows_kv > 128 ? LS_MFMA_CASE(64, 8) : LS_MFMA_CASE(64, 4);
+    const bool paged = p.block_table != nullptr;
+    // Above 128 query rows per KV head: 8 waves, two per SIMD, 256 rows per workgroup (the split
+    // planner counts on kPrefixRowsPerWorkgroup = 256); else 4 waves.
+#define LS_MFMA_CASE2(DD, WW)                                                                     \
+    (paged ? (f16 ? launch_one<DD, WW, true, true>(p, plan, out, mask_job, stream)               \
+                  : launch_one<DD, WW, false, true>(p, plan, out, mask_job, stream))             \
+           : (f16 ? launch_one<DD, WW, true, false>(p, plan, out, mask_job, stream)              \
+                  : launch_one<DD, WW, false, false>(p, plan, out, mask_job, stream)))
+#define LS_MFMA_CASE(DD) (rows_kv > 128 ? LS_MFMA_CASE2(DD, 8) : LS_MFMA_CASE2(DD, 4))
+    if (p.head_dim == 128) return LS_MFMA_CASE(128);
+    if (p.head_dim == 64) return LS_MFMA_CASE(64);
 #undef LS_MFMA_CASE
+#undef LS_MFMA_CASE2
     return hipErrorInvalidValue;
 }
 

@@ -169,21 +169,17 @@ def even_cut_bytes(d, e=2):
 
 
 def test_workspace_follows_the_schedule_of_the_whole_call():
-    """The whole-path calls cut the keys unevenly only when the last query block of a KV head is
-    light (at most 128 of 256 rows) and everything fits one round of workgroups; then the full
-    blocks get more pieces than the even cut, which shows in the workspace size.  (Without a
-    device the library plans for 256 compute units.)"""
-    even = [good_desc(hq=32, hkv=8, t=64, p=32768),            # 256 rows: one full block
-            good_desc(hq=32, hkv=8, t=16, p=32768),            # 64 rows: one block
-            good_desc(hq=40, hkv=8, t=128, p=65536, b=4),      # 640 rows, light third block, but several rounds
-            good_desc(hq=20, hkv=4, t=77, p=4000, b=2),        # 385 rows: the second block is not light
-            good_desc(dtype=ls.LS_F32, hq=32, hkv=8, t=68, p=32768, d=64)]
-    for d in even:
-        assert ls.ls_workspace_bytes(d) == even_cut_bytes(d, 4 if d.dtype == ls.LS_F32 else 2)
-    for d in (good_desc(hq=32, hkv=8, t=68, p=32768), good_desc(hq=32, hkv=8, t=69, p=3000),
+    """The whole-path calls cut the keys exactly like the stand-alone cached-key call, whatever the
+    number of query rows per KV head.  (Without a device the library plans for 256 compute units.)"""
+    for d in (good_desc(hq=32, hkv=8, t=64, p=32768),            # 256 rows: one full block
+              good_desc(hq=32, hkv=8, t=16, p=32768),            # 64 rows: one block
+              good_desc(hq=40, hkv=8, t=128, p=65536, b=4),      # 640 rows: a light third block
+              good_desc(hq=20, hkv=4, t=77, p=4000, b=2),        # 385 rows
+              good_desc(hq=32, hkv=8, t=69, p=3000),             # 276 rows: 256 + 20
               good_desc(dtype=ls.LS_F16, hq=12, hkv=2, t=60, p=2500, d=64)):
-        assert ls.ls_workspace_bytes(d) > even_cut_bytes(d)
-        assert ls.ls_workspace_bytes(d) == ls.ls_workspace_bytes(d)
+        assert ls.ls_workspace_bytes(d) == even_cut_bytes(d)
+    d = good_desc(dtype=ls.LS_F32, hq=32, hkv=8, t=68, p=32768, d=64)
+    assert ls.ls_workspace_bytes(d) == even_cut_bytes(d, 4)
 
 
 def test_split_plan_and_workspace_are_stable_and_sane():
