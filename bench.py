@@ -20,15 +20,17 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
 # HBM bytes per launch of the cached-key kernel (fetched + written) from the rocprofv3 FETCH_SIZE /
 # WRITE_SIZE runs summarised in profiles/verify_call_C3_mi355x.md, scaled by the copy calibration.
-# They cannot be read while this script runs; None for workloads without a committed profile.
-MEASURED_TRAFFIC_BYTES = {"C3": 138653109 + 17118618}
+# Hardware counters cannot be read while this script runs: the figure is copied from that
+# profile and labelled so in the output; None for workloads without a committed profile.
+PROFILED_TRAFFIC_BYTES = {"C3": 138745958 + 17957171}
+PROFILED_TRAFFIC_SOURCE = "profiles/verify_call_C3_mi355x.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not this run)"
+PREWARM_SECONDS = 0.35         # untimed calls before --warmup: the shader clock needs ~0.2 s of work to settle
 
 
 def algorithmic_bytes_prefix(w, prefix_lens):
@@ -60,7 +62,6 @@ def bench_accept_commit(args, w):
     import numpy as np
     import torch
 
-    import oracle
     from paper_2502_17421_amd import binding as ls
     from paper_2502_17421_amd import synth
 
@@ -104,6 +105,7 @@ def bench_accept_commit(args, w):
     moved = int(lens.sum()) * 2 * w.n_kv_heads * w.head_dim * e * 2   # K and V rows, read + written
     cpu = None
     if not args.no_cpu_baseline:
+        import oracle   # test infrastructure; imported for this leg only
         reps = 2000
         t0 = time.perf_counter()
         for _ in range(reps):
@@ -129,7 +131,7 @@ def bench_accept_commit(args, w):
 class ClockSampler:
     """Samples the shader clock and board power the driver reports (sysfs) while a timed region runs."""
 
-    def __init__(self, period_s=0.002):
+    def __init__(self, period_s=0.001):
         import glob
         import threading
         self.sclk_files = glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")[:1]
@@ -164,16 +166,18 @@ class ClockSampler:
             v = sorted(v)
             return {"n": len(v), "min": v[0], "median": v[len(v) // 2], "max": v[-1]} if v else None
         return {"sclk_mhz": stats(self.sclk), "power_w": stats(self.power),
-                "source": "sysfs pp_dpm_sclk / hwmon power1_input, sampled during the timed steps"}
+                "source": "sysfs pp_dpm_sclk / hwmon power1_input, sampled from the start of the pre-warm to the end "
+                          "of the timed steps"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # defaults: the card needs a few milliseconds of sustained work to reach its steady clocks
-    # (the first ~200 calls after start-up run about 15 % slower), so warm up past that
+    # Whatever --warmup says, PREWARM_SECONDS of untimed calls run first (the first calls after
+    # start-up run about 15 % slower while the clocks ramp): a short run gives the same figure
+    # as a long one.
     ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="C3",
                     help="C1..C5 (the headline metric is quoted on C3); D1, D2: cross-attention over the cache only; "
                          "A3, A5: greedy acceptance + KV commit; W1: draft self-attention; H3: C3 in fp16; "
@@ -181,11 +185,11 @@ def main():
     ap.add_argument("--page-size", type=int, default=0,
                     help="keep the cache in shuffled pages of this many rows and call ls_hybrid_tree_attn_paged")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--hot", action="store_true", help="also time with one K/V copy (cache-resident)")
+    ap.add_argument("--no-hot", action="store_true", help="skip the timing with one K/V copy (cache-resident)")
     ap.add_argument("--token-major", action="store_true",
                     help="store Q, K, V and out as [B,L,H,D] (each head's row a run of D elements) and pass strides")
-    ap.add_argument("--graph", action="store_true",
-                    help="also time replays of a HIP graph that holds one cycle over the K/V copies")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the timing of replays of a HIP graph that holds one cycle over the K/V copies")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 device copies of 512 MiB (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -195,14 +199,21 @@ def main():
     import numpy as np
     import torch
 
+    import ctypes
+
     from paper_2502_17421_amd import binding as ls
+    from paper_2502_17421_amd import build as ls_build
     from paper_2502_17421_amd import synth
-    from util import DeviceBatch
+    from paper_2502_17421_amd.device_batch import DeviceBatch
 
     if not os.path.exists(ls.LIB_PATH):
-        from paper_2502_17421_amd import build as ls_build
         ls_build.build_library()
+    if not os.path.exists(ls_build.PROBE_LIB_PATH):
+        ls_build.build_probe_library()
     ls.lib()
+    probe = ctypes.CDLL(ls_build.PROBE_LIB_PATH)   # measurement helpers, a library of their own
+    probe.ls_probe_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    probe.ls_probe_mfma_loop.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
@@ -268,10 +279,21 @@ def main():
             ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.k_tree, db.v_tree,
                                    db.parents, db.out, db.lse, ws, stream=stream)
 
-    for i in range(args.warmup):
-        call(i)
-    torch.cuda.synchronize()
+    def prewarm(fn):
+        """Untimed calls for PREWARM_SECONDS; returns how many were made."""
+        n, t_end = 0, time.perf_counter() + PREWARM_SECONDS
+        while time.perf_counter() < t_end:
+            for _ in range(50):
+                fn(n)
+                n += 1
+            torch.cuda.synchronize()
+        return n
+
     with ClockSampler() as sampler:
+        prewarm_calls = prewarm(call)
+        for i in range(args.warmup):
+            call(i)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
             call(i)
@@ -303,6 +325,7 @@ def main():
         ls.ls_prefix_attn_splitkv(db.desc, db.q, kc_alone[r], vc_alone[r], db.prefix_lens, 0, o_part, l_part,
                                   stream=stream)
 
+    prewarm(prefix_only)
     for i in range(args.warmup):
         prefix_only(i)
     torch.cuda.synchronize()
@@ -321,7 +344,8 @@ def main():
     klat = np.asarray([a.elapsed_time(b) * 1e3 for a, b in evs])
 
     hot_us = None
-    if args.hot:
+    if not args.no_hot:
+        prewarm(lambda i: call(i, 0))
         for i in range(args.warmup):
             call(i, 0)
         torch.cuda.synchronize()
@@ -332,7 +356,7 @@ def main():
         hot_us = (time.perf_counter() - t0) / args.steps * 1e6
 
     graph_us = None
-    if args.graph:
+    if not args.no_graph:
         # one cycle over the K/V copies recorded once; a replay issues it with no host work per call
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
@@ -340,8 +364,7 @@ def main():
             for r in range(n_rot):
                 call(r, r, cap)
         reps = max(1, args.steps // n_rot)
-        for _ in range(max(1, args.warmup // n_rot)):
-            g.replay()
+        prewarm(lambda i: g.replay() if i % n_rot == 0 else None)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(reps):
@@ -353,18 +376,29 @@ def main():
     buf = torch.full((1 << 30,), 1, dtype=torch.uint8, device="cuda")
     sink = torch.zeros(64, dtype=torch.float32, device="cuda")
     p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    raw_stream = ctypes.c_void_p(stream.cuda_stream)
+
+    def stream_read():
+        assert probe.ls_probe_stream_read(ctypes.c_void_p(buf.data_ptr()), buf.numel(), ctypes.c_void_p(sink.data_ptr()),
+                                          raw_stream) == 0
+
+    def mfma_loop(iters):
+        fl_out = ctypes.c_int64(0)
+        assert probe.ls_probe_mfma_loop(iters, ctypes.c_void_p(sink.data_ptr()), ctypes.byref(fl_out), raw_stream) == 0
+        return int(fl_out.value)
+
     for _ in range(3):
-        ls.ls_probe_stream_read(buf, sink, stream=stream)
+        stream_read()
     p0.record(stream)
     for _ in range(10):
-        ls.ls_probe_stream_read(buf, sink, stream=stream)
+        stream_read()
     p1.record(stream)
     torch.cuda.synchronize()
     read_gbs = 10 * buf.numel() / (p0.elapsed_time(p1) * 1e-3) / 1e9
     del buf
-    ls.ls_probe_mfma_loop(2000, sink, stream=stream)
+    mfma_loop(2000)
     p0.record(stream)
-    mf = ls.ls_probe_mfma_loop(20000, sink, stream=stream)
+    mf = mfma_loop(20000)
     p1.record(stream)
     torch.cuda.synchronize()
     mfma_tflops = mf / (p0.elapsed_time(p1) * 1e-3) / 1e12
@@ -380,7 +414,8 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": bytes_prefix / kernel_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)
+    roof["traffic"] = PROFILED_TRAFFIC_BYTES.get(w.name) if table is None and not args.token_major else None
+    roof["traffic_source"] = PROFILED_TRAFFIC_SOURCE if roof["traffic"] is not None else None
     roof["frac_of_practical_peak"] = roof["achieved"] / (read_gbs if roof["bound"] == "hbm" else mfma_tflops)
     roof["kernel"] = "prefix_mfma_kernel (ls_prefix_attn_splitkv)"
     roof["kernel_us"] = kernel_us
@@ -392,8 +427,15 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        import oracle
-        from util import oracle_full
+        import oracle   # test infrastructure; imported for this leg only
+
+        def oracle_full(batch, rows_per_seq, rng, **kw):
+            for sq in batch.seqs:
+                hq, t, _ = sq.q.shape
+                flat = rng.choice(hq * t, size=min(rows_per_seq, hq * t), replace=False)
+                rows = np.stack([flat // t, flat % t], axis=1).astype(np.int32)
+                oracle.attn_rows(sq.q, sq.k_cache, sq.v_cache, sq.k_tree, sq.v_tree, sq.parents, rows=rows, **kw)
+
         budget = 12.0
         rows_total = w.batch * w.n_q_heads * w.n_tree
         rng = np.random.default_rng(7)
@@ -420,6 +462,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "prewarm_calls": prewarm_calls,
         "ms_per_step": us_per_call / 1e3,
         "higher_is_better": False,
         "scaling": "weak",

@@ -112,17 +112,19 @@ int ls_validate_parents_host(const int32_t *parents, int32_t batch, int32_t n_tr
 
 /*
  * Number of key-axis splits the library would pick for the cached part of this
- * problem (>= 1; depends only on the descriptor, so it is stable across calls): what
- * ls_prefix_attn_splitkv uses for n_splits = 0.  The whole-path calls may cut the keys
- * differently (more pieces for the full 256-row query blocks of a KV head, fewer for a light
- * last block); their workspace size accounts for that.
+ * problem (>= 1): what ls_prefix_attn_splitkv uses for n_splits = 0, and what the whole-path
+ * calls use.  It depends on the descriptor AND on the number of compute units of the current
+ * HIP device (the splits are sized to fill the GPU once); without a device it is computed
+ * for 256 compute units (MI355X).  It is stable across calls on one device.  Ask for it, and
+ * for ls_workspace_bytes, with the device current on which the call will run.
  */
 int ls_prefix_num_splits(const ls_desc *desc, int32_t *n_splits_out);
 
 /*
  * Bytes of DEVICE workspace ls_hybrid_tree_attn needs for this descriptor:
  * the tree mask, one error word per sequence, and the partial outputs (stored in the
- * problem's dtype) and LSEs of the cached part, one per key split of the call's own schedule.
+ * problem's dtype) and LSEs of the cached part, one per key split (ls_prefix_num_splits, so
+ * the size depends on the current device's compute-unit count in the same way).
  * The workspace must be 256-byte aligned.
  */
 int ls_workspace_bytes(const ls_desc *desc, size_t *bytes_out);
@@ -210,7 +212,7 @@ int ls_workspace_error(const ls_desc *desc, void *workspace, int32_t **err_word_
 /* ---- the four subsystems, callable on their own ------------------------------------ */
 
 /*
- * (a) Tree mask (Section 2.1: masks derived from the prefix tree).  Row i gets bit j set
+ * (a) Tree mask (Section 3.3: masks derived from the prefix tree).  Row i gets bit j set
  * iff j == i or j is an ancestor of i.
  *   parents   DEVICE int32[batch, n_tree]
  *   mask      DEVICE uint64[batch, n_tree, ceil(n_tree/64)]; bit j in word j/64, bit j%64
@@ -268,7 +270,7 @@ int ls_lse_merge(const ls_desc *desc, int32_t n_parts, int32_t part_dtype,
 
 /*
  * Greedy (temperature 0) acceptance of the speculation tree, once the target model has run
- * over it (Section 2.1 "Fast Tree Attention": all candidate sequences are verified in one
+ * over it (Section 3.3 "Fast Tree Attention": all candidate sequences are verified in one
  * pass without altering the final result; Section 4.1 evaluates at T = 0).  Node 0 holds
  * the last token already sampled and is always accepted.  From node cur the path continues
  * with the child whose token equals target_tokens[cur] (the lowest node index if several
@@ -352,20 +354,6 @@ int ls_kv_commit_paged(const ls_desc *desc, const void *k_tree, const void *v_tr
                        void *k_pages, void *v_pages,
                        const int32_t *block_table, int32_t bt_stride, int32_t page_size,
                        int32_t *new_prefix_lens, int32_t *err_flag, void *stream);
-
-/* ---- measurement helpers (nothing of the method) ---------------------------------------- */
-
-/*
- * What the card reaches in practice, for the benchmark to quote beside the kernels' figures
- * (Section 4 of the paper measures wall-clock speed; these give the ceilings on this GPU).
- * ls_probe_stream_read reads `bytes` (>= 16, 16-byte aligned DEVICE memory) once with every
- * compute unit and writes nothing but, possibly, 16 bytes at `sink` (DEVICE).
- * ls_probe_mfma_loop issues `iters` rounds of independent bf16 32x32x16 MFMAs from two waves
- * per SIMD on every compute unit; *flops_out (HOST, may be NULL) receives the flop count.
- * Both enqueue one kernel on `stream`; time them with events.
- */
-int ls_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
-int ls_probe_mfma_loop(int32_t iters, void *sink, int64_t *flops_out, void *stream);
 
 #ifdef __cplusplus
 }

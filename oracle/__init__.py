@@ -23,6 +23,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ls_oracle.c")
 _LIB = os.path.join(_HERE, "libls_oracle.so")
 _lib = None
+# LS_ORACLE_LIB: load this build of ls_oracle.c instead (the sanitizer test points it at an
+# -fsanitize=address,undefined build)
+_OVERRIDE = os.environ.get("LS_ORACLE_LIB")
 
 
 def build(force: bool = False) -> str:
@@ -38,8 +41,9 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    build()
-    lib = ctypes.CDLL(_LIB)
+    if not _OVERRIDE:
+        build()
+    lib = ctypes.CDLL(_OVERRIDE or _LIB)
     i32, i64, f64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_double
     vp = ctypes.c_void_p
     lib.ls_oracle_num_threads.restype = ctypes.c_int

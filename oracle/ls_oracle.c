@@ -12,7 +12,7 @@
  *   For one query row q of one speculative-tree token i, the keys it may see
  *   are every cached row of the main sequence (no mask) and those tree rows j
  *   that lie on the path from i up to its root, i itself included (the tree
- *   mask of Section 2.1 "Fast Tree Attention": tokens off that path are wrong
+ *   mask of Section 3.3 "Fast Tree Attention": tokens off that path are wrong
  *   combinations and are removed).  Over that visible set V(i):
  *
  *       z_j  = scale * <q, k_j>                  (appendix: q K^T / sqrt(d_qk))
@@ -289,7 +289,7 @@ int ls_oracle_lse_merge(int64_t n_rows, int32_t n_parts, int32_t head_dim,
 
 /*
  * Greedy (temperature 0) acceptance of a speculation tree -- the verification
- * step that follows the target model's pass over the tree (Section 2.1 "Fast
+ * step that follows the target model's pass over the tree (Section 3.3 "Fast
  * Tree Attention": the target verifies all candidate sequences at once without
  * altering the final result; Section 4.1 evaluates at T = 0).
  *

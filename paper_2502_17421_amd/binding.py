@@ -14,7 +14,9 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libls_attn.so")
+# LS_ATTN_LIB: load this build of the library instead of the in-tree one (the sanitizer test points it
+# at a build whose host code is instrumented)
+LIB_PATH = os.environ.get("LS_ATTN_LIB") or os.path.join(_HERE, "libls_attn.so")
 
 LS_OK = 0
 LS_ERR_NULL, LS_ERR_SHAPE, LS_ERR_DTYPE, LS_ERR_STRIDE = -1, -2, -3, -4
@@ -78,8 +80,6 @@ def lib() -> ctypes.CDLL:
     L.ls_hybrid_tree_attn_paged.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                             _vp]
     L.ls_cache_attn_paged.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]
-    L.ls_probe_stream_read.argtypes = [_vp, _sz, _vp, _vp]
-    L.ls_probe_mfma_loop.argtypes = [_i32, _vp, ctypes.POINTER(ctypes.c_int64), _vp]
     L.ls_kv_commit_paged.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
     for name in ("ls_validate_desc", "ls_validate_parents_host", "ls_prefix_num_splits", "ls_prefix_split_len",
                  "ls_workspace_bytes", "ls_workspace_error", "ls_hybrid_tree_attn", "ls_hybrid_tree_attn_single",
@@ -87,7 +87,7 @@ def lib() -> ctypes.CDLL:
                  "ls_cache_attn", "ls_build_tree_mask",
                  "ls_prefix_attn_splitkv", "ls_tree_attn_masked", "ls_lse_merge", "ls_tree_accept_greedy",
                  "ls_kv_commit", "ls_hybrid_tree_attn_paged", "ls_cache_attn_paged",
-                 "ls_kv_commit_paged", "ls_probe_stream_read", "ls_probe_mfma_loop"):
+                 "ls_kv_commit_paged"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -331,17 +331,3 @@ def ls_cache_attn_paged(desc, q, k_pages, v_pages, block_table, page_size, prefi
     if check:
         _check(st, "ls_cache_attn_paged")
     return int(st)
-
-
-def ls_probe_stream_read(src, sink, stream=None, check: bool = True) -> int:
-    st = lib().ls_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream))
-    if check:
-        _check(st, "ls_probe_stream_read")
-    return int(st)
-
-
-def ls_probe_mfma_loop(iters: int, sink, stream=None) -> int:
-    """Returns the flop count of the enqueued kernel."""
-    fl = ctypes.c_int64(0)
-    _check(lib().ls_probe_mfma_loop(int(iters), _ptr(sink), ctypes.byref(fl), _stream(stream)), "ls_probe_mfma_loop")
-    return int(fl.value)

@@ -1,5 +1,5 @@
 // The two integer steps that follow the attention in a verification round: greedy acceptance
-// of the speculation tree (Section 2.1 "Fast Tree Attention", evaluated at T = 0 in Section
+// of the speculation tree (Section 3.3 "Fast Tree Attention", evaluated at T = 0 in Section
 // 4.1) and the move of the accepted tokens' key/value rows into the cache (the cache is
 // updated only once verification is complete, Section 3.2; "KV cache movement" in the
 // appendix "Experiments Details").  Both are latency-bound: a tree has at most LS_MAX_TREE nodes.

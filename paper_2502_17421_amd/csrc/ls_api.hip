@@ -600,21 +600,4 @@ int ls_kv_commit_paged(const ls_desc *desc, const void *k_tree, const void *v_tr
                : LS_ERR_HIP;
 }
 
-int ls_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream)
-{
-    if (!src || !sink) return LS_ERR_NULL;
-    if (bytes < 16 || !aligned16(src) || !aligned16(sink)) return LS_ERR_SHAPE;
-    return launch_probe_stream_read(src, bytes, sink, (hipStream_t)stream) == hipSuccess ? LS_OK : LS_ERR_HIP;
-}
-
-int ls_probe_mfma_loop(int32_t iters, void *sink, int64_t *flops_out, void *stream)
-{
-    if (!sink) return LS_ERR_NULL;
-    if (iters <= 0 || iters > (1 << 24)) return LS_ERR_SHAPE;
-    int per_cu = 0;
-    if (launch_probe_mfma_loop(iters, (float *)sink, &per_cu, (hipStream_t)stream) != hipSuccess) return LS_ERR_HIP;
-    if (flops_out) *flops_out = (int64_t)per_cu * iters * compute_units();
-    return LS_OK;
-}
-
 }  // extern "C"

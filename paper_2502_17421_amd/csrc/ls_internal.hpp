@@ -174,7 +174,5 @@ hipError_t launch_kv_commit(const Problem &p, int dtype, const int32_t *accept_p
                             void *k_cache, void *v_cache, int32_t *new_prefix_lens, int32_t *err_flag,
                             hipStream_t stream);
 
-hipError_t launch_probe_stream_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
-hipError_t launch_probe_mfma_loop(int iters, float *sink, int *flops_per_iter_per_cu, hipStream_t stream);
 
 }  // namespace ls

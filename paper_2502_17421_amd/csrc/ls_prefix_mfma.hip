@@ -136,7 +136,7 @@ __device__ __forceinline__ void copy_to_lds(const uint8_t *base, uint32_t voff, 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_base), "v"(voff), "s"(base)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ const uint8_t *uniform_ptr(const uint8_t *p)
@@ -282,12 +282,12 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
         const int pidx = (row >> p.page_shift) - first_page;
         return (int64_t)__builtin_amdgcn_readfirstlane(((const uint32_t *)(smem + PAGE_TAB))[pidx]);
     };
-    // Requests.  issue_rows<IS_V>(k0, dst): this wave's LOADS copies of the K (or V) rows of the
-    // tile that starts at cache row k0, to the ring stage at LDS byte offset dst.  Rows past
+    // Requests.  issue_rows<IS_V>(k0, tile_base, dst): this wave's LOADS copies of the K (or V) rows
+    // of the tile that starts at cache row k0, to the ring stage at LDS byte offset dst.  Rows past
     // the end of the split repeat its last row; their scores are masked.
     // Paged: one load instruction covers ROWS_PER_LOAD consecutive rows, which never straddle a
     // page (page sizes are powers of two >= 16): its base is that of its own page.
-    auto issue_rows = [&](auto is_v_tag, int k0, uint32_t dst) __attribute__((always_inline)) {
+    auto issue_rows = [&](auto is_v_tag, int k0, const uint8_t *tile_base, uint32_t dst) __attribute__((always_inline)) {
         constexpr bool IS_V = decltype(is_v_tag)::value;
         if (!loader) return;  // wave-uniform
         const uint32_t d0 = __builtin_amdgcn_readfirstlane(smem_off + dst);
@@ -313,7 +313,7 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
                 copy_to_lds(base, (uint32_t)((src - src0) * row_bytes) + (ld_pos ^ swz(row)) * 16, d0 + row0 * ROWB);
             }
         } else {
-            const uint8_t *base = uniform_ptr((IS_V ? vbase : kbase) + k0 * row_bytes);
+            const uint8_t *base = tile_base;  // address of the tile's first row (contiguous caches only)
             if (last >= TK - 1) {
 #pragma unroll
                 for (int j = 0; j < LOADS; ++j)
@@ -347,18 +347,23 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     // Requests, in tile order: request r (r >= -(PD+1)) is the K rows of tile r+PD+1 and the V rows
     // of tile r+PD, as far as these tiles exist; a request with both parts is INFLIGHT load
     // instructions per wave.  The state below is that of the next request.
+    // (Tile addresses advance by a fixed step and start over where the tile order wraps around.)
+    const uint8_t *const k_ptr_lo = uniform_ptr(kbase + k_lo * k_row_bytes), *const v_ptr_lo = uniform_ptr(vbase + k_lo * v_row_bytes);
     int rq_kt = 0, rq_k0 = key_first, rq_vt = 0, rq_v0 = key_first;
+    const uint8_t *rq_kptr = uniform_ptr(kbase + key_first * k_row_bytes), *rq_vptr = uniform_ptr(vbase + key_first * v_row_bytes);
     uint32_t rq_koff = 0, rq_voff = V_RING;
     auto request_k = [&]() __attribute__((always_inline)) {
-        if (rq_kt < n_tiles) issue_rows(is_k{}, rq_k0, rq_koff);
+        if (rq_kt < n_tiles) issue_rows(is_k{}, rq_k0, rq_kptr, rq_koff);
         ++rq_kt;
         rq_k0 = next_key0(rq_k0);
+        rq_kptr = rq_k0 == k_lo ? k_ptr_lo : rq_kptr + TK * k_row_bytes;
         rq_koff = next_k(rq_koff);
     };
     auto request_v = [&]() __attribute__((always_inline)) {
-        if (rq_vt < n_tiles) issue_rows(is_v{}, rq_v0, rq_voff);
+        if (rq_vt < n_tiles) issue_rows(is_v{}, rq_v0, rq_vptr, rq_voff);
         ++rq_vt;
         rq_v0 = next_key0(rq_v0);
+        rq_vptr = rq_v0 == k_lo ? v_ptr_lo : rq_vptr + TK * v_row_bytes;
         rq_voff = next_v(rq_voff);
     };
     request_k();  // request -(PD+1)
@@ -608,7 +613,12 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
         for (int kk = 0; kk < KSTEPS; ++kk) s_sl[0] = mfma32<F16>(k0f[kk], q_reg[kk], s_sl[0]);
     }
     if (key_first + TK > k_hi) mask_tail(s_sl[0], key_first);
-    raise_reference(s_sl[0]);  // sets m_run from the first 32 keys (at least one of them is valid)
+    {  // the reference exponent: the largest of the first 32 scores (at least one key is valid)
+        float mx = s_sl[0][0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_sl[0][e]);
+        m_run = half_max(mx);
+    }
     mc = m_run * c;
     advance0();
     if (n_tiles > 1) {

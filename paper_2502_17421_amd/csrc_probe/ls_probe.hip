@@ -1,9 +1,9 @@
-// Two measurement helpers behind the C ABI, used by the benchmark to put the kernels' figures
-// next to what this card reaches in practice: a pure streaming read and a bf16 MFMA issue loop.
-// They compute nothing of the method.
-#include "ls_internal.hpp"
-
-namespace ls {
+// Measurement helpers for the benchmark, built into a library of their own (libls_probe.so): what
+// this card reaches in practice on a pure streaming read and on a bf16 MFMA issue loop, to put
+// next to the kernels' figures.  They compute nothing of the method and are not part of the
+// attention library or its header.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace {
 
@@ -48,25 +48,31 @@ __global__ void __launch_bounds__(512) mfma_loop_kernel(int iters, float *sink)
 
 }  // namespace
 
-hipError_t launch_probe_stream_read(const void *src, size_t bytes, void *sink, hipStream_t stream)
+extern "C" {
+
+// Reads `bytes` (>= 16, 16-byte aligned DEVICE memory) once with every compute unit; writes nothing
+// but, possibly, 16 bytes at `sink` (DEVICE).  Returns 0, or -1 on a bad argument / launch error.
+int ls_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream)
 {
-    int cus = 256;
-    int dev = 0;
+    if (!src || !sink || bytes < 16 || ((uintptr_t)src & 15u) || ((uintptr_t)sink & 15u)) return -1;
+    int cus = 256, dev = 0;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    hipLaunchKernelGGL(stream_read_kernel, dim3(cus * 8), dim3(256), 0, stream, (const u32x4 *)src, bytes / 16,
-                       (u32x4 *)sink);
-    return hipGetLastError();
+    hipLaunchKernelGGL(stream_read_kernel, dim3(cus * 8), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)src,
+                       bytes / 16, (u32x4 *)sink);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-hipError_t launch_probe_mfma_loop(int iters, float *sink, int *flops_per_iter_per_cu, hipStream_t stream)
+// `iters` rounds of independent bf16 32x32x16 MFMAs from two waves per SIMD on every compute unit;
+// *flops_out (HOST, may be NULL) receives the flop count of the launch.
+int ls_probe_mfma_loop(int32_t iters, void *sink, int64_t *flops_out, void *stream)
 {
-    int cus = 256;
-    int dev = 0;
+    if (!sink || iters <= 0 || iters > (1 << 24)) return -1;
+    int cus = 256, dev = 0;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    hipLaunchKernelGGL(mfma_loop_kernel, dim3(cus), dim3(512), 0, stream, iters, sink);
+    hipLaunchKernelGGL(mfma_loop_kernel, dim3(cus), dim3(512), 0, (hipStream_t)stream, iters, (float *)sink);
     // 8 waves x 4 chains x one 32x32x16 MFMA (2*32*32*16 flop) per iteration and workgroup
-    if (flops_per_iter_per_cu) *flops_per_iter_per_cu = 8 * 4 * 2 * 32 * 32 * 16;
-    return hipGetLastError();
+    if (flops_out) *flops_out = (int64_t)8 * 4 * 2 * 32 * 32 * 16 * iters * cus;
+    return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-}  // namespace ls
+}  // extern "C"

@@ -273,3 +273,17 @@ def test_product_code_does_not_touch_the_oracle():
     for f in ("ls_oracle.c", "__init__.py"):
         text = open(os.path.join(ROOT, "oracle", f)).read()
         assert "paper_2502_17421_amd" not in text and "ls_attn.h" not in text
+
+
+def test_cached_key_kernels_use_no_scratch_memory():
+    """The MFMA kernel orders its LDS reads behind its HBM->LDS copies by counting outstanding
+    vector-memory instructions (s_waitcnt vmcnt(N)).  A register spill would add scratch loads
+    and stores to that count behind the compiler's back, so no instantiation may spill."""
+    if not os.path.exists(ls_build.RESOURCE_REPORT) or ls_build.is_stale():
+        ls_build.build_library()
+    res = ls_build.kernel_resources()
+    kernels = {k: v for k, v in res.items() if "prefix_mfma_kernel" in k}
+    assert len(kernels) >= 16, sorted(res)
+    for name, r in kernels.items():
+        assert r.get("ScratchSize", 0) == 0 and r.get("VGPRs Spill", 0) == 0, (name, r)
+        assert r.get("VGPRs", 0) + r.get("AGPRs", 0) <= 256, (name, r)   # two waves per SIMD
