@@ -287,3 +287,19 @@ def test_cached_key_kernels_use_no_scratch_memory():
     for name, r in kernels.items():
         assert r.get("ScratchSize", 0) == 0 and r.get("VGPRs Spill", 0) == 0, (name, r)
         assert r.get("VGPRs", 0) + r.get("AGPRs", 0) <= 256, (name, r)   # two waves per SIMD
+
+
+def test_only_the_tile_copies_touch_m0(tmp_path):
+    """The HBM->LDS copies of the MFMA kernel set M0 inside inline assembly, which cannot declare
+    it clobbered.  That is sound as long as the compiler itself never uses M0 in that file: in
+    the generated assembly every line that names M0 is the scalar move in front of one copy."""
+    asm = tmp_path / "prefix_mfma.s"
+    src = os.path.join(ls_build.CSRC, "ls_prefix_mfma.hip")
+    flags = [f for f in ls_build.FLAGS if f not in ("-shared", "-fPIC")]
+    subprocess.run([ls_build.HIPCC, *flags, "-S", "--cuda-device-only", "-o", str(asm), src], check=True,
+                   stderr=subprocess.DEVNULL)
+    lines = asm.read_text().splitlines()
+    copies = sum("global_load_lds_dwordx4" in ln for ln in lines)
+    m0 = [ln.strip() for ln in lines if re.search(r"\bm0\b", ln.split(";")[0])]
+    assert copies > 0 and len(m0) == copies
+    assert all(re.fullmatch(r"s_mov_b32 m0, s\d+", ln) for ln in m0), [ln for ln in m0 if not ln.startswith("s_mov_b32")][:5]

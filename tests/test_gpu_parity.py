@@ -258,6 +258,34 @@ def test_full_path_other_shapes(dtype, hq, hkv, d, t, plens):
     say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, dtype, "  result", stress=True))
 
 
+@pytest.mark.parametrize("dtype,hq,hkv,d,t,depth,plens", [
+    ("bf16", 2, 1, 128, 8, 4, [30000]),       # one KV head, few rows: > 32 parts, a wavefront per row, several batches
+    ("bf16", 4, 1, 64, 8, 4, [20000]),        # the same with head_dim 64: 2-byte pieces per lane
+    ("f16", 8, 2, 128, 16, 6, [16000]),       # 17 .. 32 parts, a wavefront per row
+    ("bf16", 3, 3, 128, 7, 3, [5000]),        # 21 rows: the last wavefront is part empty; no query grouping
+    ("bf16", 10, 2, 128, 300, 40, [1500]),    # five mask words, up to 41 visible keys per row, group of five
+    ("bf16", 40, 8, 128, 33, 8, [900, 40]),   # at most four parts, 16 lanes per row
+    ("f32", 4, 2, 128, 70, 12, [3000]),       # float rows of 512 bytes, two mask words
+])
+def test_tail_kernel_forms(dtype, hq, hkv, d, t, depth, plens):
+    """Whole-path calls whose shapes select each form of the kernel that ends the call (lanes per
+    query row, split rows per request, one or two register sets), checked against the oracle."""
+    rng = np.random.default_rng(7100 + hq * t)
+    seqs = []
+    for pl in plens:
+        parents = synth.tree_constrained(rng, t, depth, 4)
+        seqs.append(synth.make_sequence(rng, dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n_tree=t,
+                                        prefix_len=pl, parents=parents, variant="peaked"))
+    w = synth.Workload("case", dtype, len(seqs), hq, hkv, d, t, min(plens), max(plens), None, None, 0)
+    batch = synth.Batch(w, "peaked", seqs)
+    db = DeviceBatch(batch)
+    say(f"tail forms {dtype} hq={hq} hkv={hkv} d={d} t={t} plens={plens} splits={ls.ls_prefix_num_splits(db.desc)}")
+    out, lse = db.run_full()
+    torch.cuda.synchronize()
+    ro, rl = oracle_full(batch)
+    say(gates(out.float().cpu().numpy(), lse.cpu().numpy(), ro, rl, dtype, "  result", stress=True))
+
+
 def test_full_path_token_major_layout():
     batch = small("C2", 1300, "peaked")
     db = DeviceBatch(batch, token_major=True)
