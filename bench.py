@@ -184,6 +184,9 @@ def main():
                          "L3: C3 with a 256-node tree; B3: C3 with the 68-node beam tree")
     ap.add_argument("--page-size", type=int, default=0,
                     help="keep the cache in shuffled pages of this many rows and call ls_hybrid_tree_attn_paged")
+    ap.add_argument("--single-launch", action="store_true",
+                    help="time ls_hybrid_tree_attn_fused (the last workgroup of each query block merges) instead "
+                         "of the two-launch call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hot", action="store_true", help="skip the timing with one K/V copy (cache-resident)")
     ap.add_argument("--token-major", action="store_true",
@@ -242,6 +245,7 @@ def main():
     k_rot = [db.k_cache] + [same_order(db.k_cache) for _ in range(n_rot - 1)]
     v_rot = [db.v_cache] + [same_order(db.v_cache) for _ in range(n_rot - 1)]
     ws = torch.empty(ls.ls_workspace_bytes(db.desc), dtype=torch.uint8, device="cuda")
+    ls.ls_workspace_init(ws)   # the arrival counters of --single-launch; nothing else reads them
     n_splits = ls.ls_prefix_num_splits(db.desc)
     stream = torch.cuda.current_stream()
 
@@ -275,6 +279,9 @@ def main():
                                          db.k_tree, db.v_tree, db.parents, db.out, db.lse, ws, stream=stream)
         elif w.kind == "cross":  # cached keys only: the draft model's cross-attention over the target cache
             ls.ls_cache_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.out, db.lse, ws, stream=stream)
+        elif args.single_launch:
+            ls.ls_hybrid_tree_attn_fused(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.k_tree, db.v_tree,
+                                         db.parents, db.out, db.lse, ws, stream=stream)
         else:
             ls.ls_hybrid_tree_attn(db.desc, db.q, k_rot[r], v_rot[r], db.prefix_lens, db.k_tree, db.v_tree,
                                    db.parents, db.out, db.lse, ws, stream=stream)
@@ -471,7 +478,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q heads / {w.n_kv_heads} kv heads, head_dim "
                                f"{w.head_dim}, prefix {plens}, n_tree {w.n_tree}, seed {w.seed}",
-                   "kv_layout": ("[B,P,Hkv,D] (token-major)" if args.token_major else "[B,Hkv,P,D]") if table is None else f"shuffled pages [page,Hkv,{args.page_size},D]", "n_splits": n_splits, "kv_rotation_copies": n_rot,
+                   "kv_layout": ("[B,P,Hkv,D] (token-major)" if args.token_major else "[B,Hkv,P,D]") if table is None else f"shuffled pages [page,Hkv,{args.page_size},D]", "n_splits": n_splits, "launches": 1 if args.single_launch else 2, "kv_rotation_copies": n_rot,
                    "kv_rotation_bytes": n_rot * kv_bytes},
         "call_us": {"mean_wall": us_per_call, "event_min": float(lat.min()), "event_median": float(np.median(lat)),
                     "event_p90": float(np.percentile(lat, 90))},

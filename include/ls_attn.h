@@ -187,6 +187,38 @@ int ls_hybrid_tree_attn_static(const ls_desc *desc, const void *q,
                                void *out, float *lse, void *stream);
 
 /*
+ * The whole call as ONE kernel launch (Section 3.3: the two attention results are aggregated;
+ * here the aggregation runs inside the kernel that computes the cached-key part).  Every
+ * workgroup of the cached-key kernel, once its partial rows are written and fenced, adds one
+ * to a counter of its (sequence, KV head, query block); the workgroup that finds all the
+ * others already counted builds the tree mask, does the masked tree attention and merges, in
+ * fixed part order, for that block's rows.  Nothing waits for anything (no wait can fail to
+ * end), and the result does not depend on which workgroup arrives last: the same inputs give
+ * bit-identical outputs.  The results agree with ls_hybrid_tree_attn to rounding (the row sums
+ * are taken in another lane order), not bit for bit.
+ *
+ *   - Arguments, workspace size and error words as for ls_hybrid_tree_attn.
+ *   - The counters are the first LS_WORKSPACE_COUNTER_BYTES of the workspace, whatever the
+ *     descriptor.  They must be zero when the call starts and are zero again when it ends:
+ *     call ls_workspace_init once on a fresh workspace (and again after anything else wrote
+ *     there).  ls_workspace_init enqueues a small kernel, never a memset, so both calls may sit
+ *     in a captured HIP graph.  No other entry point reads or writes the counters.
+ *   - Problems outside the matrix-core kernel (float inputs, row strides beyond its reach) or
+ *     with more than 4096 (sequence, KV head, query block) triples run as
+ *     ls_hybrid_tree_attn does, in two launches.
+ *   - Which form is faster depends on the shape: the merging workgroups work alone while the
+ *     rest of the chip has finished or is still busy with other blocks.  Measured figures are
+ *     in the design notes; ls_hybrid_tree_attn is the default.
+ */
+#define LS_WORKSPACE_COUNTER_BYTES (4096u * 4u)
+int ls_workspace_init(void *workspace /* DEVICE, 256-byte aligned */, size_t workspace_bytes, void *stream);
+int ls_hybrid_tree_attn_fused(const ls_desc *desc, const void *q,
+                              const void *k_cache, const void *v_cache, const int32_t *prefix_lens,
+                              const void *k_tree, const void *v_tree, const int32_t *parents,
+                              void *out, float *lse,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Unmasked attention of the query rows over the cached keys only, merged over the key
  * splits: out = o_cache, lse = LSE_cache of the appendix.  This is the cross-attention over
  * the target model's KV cache that the draft model of Section 3.1 runs at every drafting

@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
     L.ls_hybrid_tree_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_hybrid_tree_attn_single.argtypes = [dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_hybrid_tree_attn_static.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+    L.ls_hybrid_tree_attn_fused.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.ls_workspace_init.argtypes = [_vp, _sz, _vp]
     L.ls_cache_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_build_tree_mask.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
     L.ls_prefix_attn_splitkv.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
@@ -228,6 +230,30 @@ def ls_hybrid_tree_attn_static(desc, q, k_cache, v_cache, prefix_lens, k_tree, v
                                           _ptr(lse), _stream(stream))
     if check:
         _check(st, "ls_hybrid_tree_attn_static")
+    return int(st)
+
+
+LS_WORKSPACE_COUNTER_BYTES = 4096 * 4
+
+
+def ls_workspace_init(workspace, stream=None, check: bool = True) -> int:
+    """Zero the arrival counters at the start of a workspace (needed once before ls_hybrid_tree_attn_fused)."""
+    st = lib().ls_workspace_init(_ptr(workspace), _sz(0 if workspace is None else workspace.numel() *
+                                                      workspace.element_size()), _stream(stream))
+    if check:
+        _check(st, "ls_workspace_init")
+    return int(st)
+
+
+def ls_hybrid_tree_attn_fused(desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree, parents, out, lse, workspace,
+                              stream=None, check: bool = True) -> int:
+    """The whole path in one launch: the last workgroup of each query block merges (counters at the workspace start)."""
+    st = lib().ls_hybrid_tree_attn_fused(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(prefix_lens),
+                                         _ptr(k_tree), _ptr(v_tree), _ptr(parents), _ptr(out), _ptr(lse),
+                                         _ptr(workspace), _sz(0 if workspace is None else workspace.numel() *
+                                                              workspace.element_size()), _stream(stream))
+    if check:
+        _check(st, "ls_hybrid_tree_attn_fused")
     return int(st)
 
 

@@ -103,6 +103,10 @@ int compute_units()
     return cached;
 }
 
+// The first bytes of every workspace are the arrival counters of the single-launch call, at a
+// place that does not depend on the problem: one ls_workspace_init serves every later call.
+constexpr size_t kArrivalBytes = (size_t)kMaxArrivalCounters * sizeof(uint32_t);
+
 struct Workspace {
     size_t off_mask, off_err, off_lse, off_o, total;
     int32_t n_parts;
@@ -114,7 +118,7 @@ Workspace layout(const ls_desc &d, const SplitPlan &plan)
     const size_t words = (d.n_tree + 63) / 64;
     w.n_parts = plan.n_splits;
     const size_t rows = (size_t)d.batch * d.n_q_heads * w.n_parts * d.n_tree;
-    w.off_mask = 0;
+    w.off_mask = align_up(kArrivalBytes);
     w.off_err = align_up(w.off_mask + (size_t)d.batch * d.n_tree * words * sizeof(uint64_t));
     w.off_lse = align_up(w.off_err + (size_t)d.batch * sizeof(int32_t));
     w.off_o = align_up(w.off_lse + rows * sizeof(float));
@@ -308,7 +312,7 @@ int ls_prefix_attn_splitkv(const ls_desc *desc, const void *q, const void *k_cac
     const Partials out{o_part, lse_part, plan.n_splits, 0, is_16bit(part_dtype)};
     hipError_t e;
     if (prefix_mfma_supports(p, desc->dtype)) {
-        e = launch_prefix_mfma(p, desc->dtype, plan, out, MaskJob{nullptr, nullptr, nullptr}, (hipStream_t)stream);
+        e = launch_prefix_mfma(p, desc->dtype, plan, out, MaskJob{nullptr, nullptr, nullptr}, FusedTail{}, (hipStream_t)stream);
     } else {
         if (part_dtype != LS_F32) return LS_ERR_UNSUPPORTED;
         e = launch_prefix_valu(p, desc->dtype, plan, out, MaskJob{nullptr, nullptr, nullptr}, (hipStream_t)stream);
@@ -351,7 +355,7 @@ namespace {
 int hybrid_contiguous(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
                       const int32_t *prefix_lens, int32_t prefix_len_all, const void *k_tree, const void *v_tree,
                       const int32_t *parents, void *out, float *lse, void *workspace, size_t workspace_bytes,
-                      void *stream)
+                      void *stream, bool single_launch = false)
 {
     const int rc = validate(desc);
     if (rc) return rc;
@@ -377,7 +381,21 @@ int hybrid_contiguous(const ls_desc *desc, const void *q, const void *k_cache, c
     // the same launch carries the workgroups of (a), the tree mask
     const Partials cache_out{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype), 1};
     if (prefix_mfma_supports(p, desc->dtype)) {
-        if (launch_prefix_mfma(p, desc->dtype, plan, cache_out, MaskJob{parents, mask, err}, s) != hipSuccess) return LS_ERR_HIP;
+        // Single launch: the last workgroup of each (sequence, KV head, query block) does (c) and (d)
+        // for that block's rows; the mask workgroups still fill the workspace's mask and error words.
+        const bool fused =
+            single_launch && (int64_t)desc->batch * desc->n_kv_heads * prefix_mfma_query_blocks(p) <= kMaxArrivalCounters;
+        FusedTail tail{};
+        if (fused) {
+            tail.arrivals = (uint32_t *)base;
+            tail.parents = parents;
+            tail.out = out;
+            for (int i = 0; i < 3; ++i) tail.o_stride[i] = desc->o_stride[i];
+            tail.lse = lse;
+        }
+        if (launch_prefix_mfma(p, desc->dtype, plan, cache_out, MaskJob{parents, mask, err}, tail, s) != hipSuccess)
+            return LS_ERR_HIP;
+        if (fused) return LS_OK;
     } else {
         const Partials f32_out{o_parts, lse_parts, w.n_parts, 0, 0, 1};
         if (is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;  // 16-bit row strides beyond the MFMA kernel's range
@@ -432,6 +450,23 @@ int ls_hybrid_tree_attn_static(const ls_desc *desc, const void *q, const void *k
                              (size_t)LS_STATIC_SCRATCH_BYTES, stream);
 }
 
+int ls_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < kArrivalBytes) return LS_ERR_WORKSPACE;
+    return launch_clear_words((uint32_t *)workspace, kMaxArrivalCounters, (hipStream_t)stream) == hipSuccess ? LS_OK
+                                                                                                          : LS_ERR_HIP;
+}
+
+int ls_hybrid_tree_attn_fused(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
+                              const int32_t *prefix_lens, const void *k_tree, const void *v_tree,
+                              const int32_t *parents, void *out, float *lse, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    if (!prefix_lens) return LS_ERR_NULL;
+    return hybrid_contiguous(desc, q, k_cache, v_cache, prefix_lens, 0, k_tree, v_tree, parents, out, lse, workspace,
+                             workspace_bytes, stream, true);
+}
+
 int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,
                   const int32_t *prefix_lens, void *out, float *lse, void *workspace, size_t workspace_bytes,
                   void *stream)
@@ -452,7 +487,7 @@ int ls_cache_attn(const ls_desc *desc, const void *q, const void *k_cache, const
     const bool mfma = prefix_mfma_supports(p, desc->dtype);
     if (!mfma && is_16bit(desc->dtype)) return LS_ERR_UNSUPPORTED;
     const Partials parts{o_parts, lse_parts, w.n_parts, 0, is_16bit(desc->dtype), 1};
-    const hipError_t e = mfma ? launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s)
+    const hipError_t e = mfma ? launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, FusedTail{}, s)
                               : launch_prefix_valu(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s);
     if (e != hipSuccess) return LS_ERR_HIP;
     // the tail kernel without a mask: merge of the split partials only
@@ -541,7 +576,7 @@ int ls_hybrid_tree_attn_paged(const ls_desc *desc, const void *q, const void *k_
     if (!prefix_mfma_supports(p, desc->dtype)) return LS_ERR_UNSUPPORTED;
     const Partials parts{base + w.off_o, (float *)(base + w.off_lse), w.n_parts, 0, 1, 1};
     hipStream_t s = (hipStream_t)stream;
-    if (launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{parents, mask, err}, s) != hipSuccess) return LS_ERR_HIP;
+    if (launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{parents, mask, err}, FusedTail{}, s) != hipSuccess) return LS_ERR_HIP;
     if (launch_tree_merge(p, desc->dtype, mask, parts, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)
         return LS_ERR_HIP;
     return LS_OK;
@@ -569,7 +604,7 @@ int ls_cache_attn_paged(const ls_desc *desc, const void *q, const void *k_pages,
     if (!prefix_mfma_supports(p, desc->dtype)) return LS_ERR_UNSUPPORTED;
     const Partials parts{base + w.off_o, (float *)(base + w.off_lse), w.n_parts, 0, 1, 1};
     hipStream_t s = (hipStream_t)stream;
-    if (launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, s) != hipSuccess)
+    if (launch_prefix_mfma(p, desc->dtype, plan, parts, MaskJob{nullptr, nullptr, nullptr}, FusedTail{}, s) != hipSuccess)
         return LS_ERR_HIP;
     if (launch_tree_merge(p, desc->dtype, nullptr, parts, plan.n_splits, out, desc->o_stride, lse, s) != hipSuccess)
         return LS_ERR_HIP;

@@ -65,6 +65,19 @@ struct MaskJob {
     int32_t *err_flag;
 };
 
+// Single-launch form of the whole call: every workgroup of the cached-key kernel counts itself in
+// at arrivals[(sequence, KV head, query block)] after its partial rows are written, and the one
+// that finds all others there does the tree attention and the merge for the rows of that block.
+// Nothing waits for anything.  arrivals == nullptr: the kernel only writes its partial rows.
+struct FusedTail {
+    uint32_t *arrivals;  // zero before the launch; the merging workgroup puts its counter back to zero
+    const int32_t *parents;
+    void *out;
+    int64_t o_stride[3];
+    float *lse;
+};
+constexpr int kMaxArrivalCounters = 4096;  // (sequence, KV head, query block) triples one single-launch call may have
+
 struct SplitPlan {
     int32_t n_splits;   // parts the cached-key kernel writes
     int32_t split_len;  // cache rows per split
@@ -156,7 +169,11 @@ hipError_t launch_tree_attn(const Problem &p, int dtype, const uint64_t *mask, c
 hipError_t launch_prefix_valu(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
                               const MaskJob &mask_job, hipStream_t stream);
 hipError_t launch_prefix_mfma(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
-                              const MaskJob &mask_job, hipStream_t stream);
+                              const MaskJob &mask_job, const FusedTail &tail, hipStream_t stream);
+// query blocks per KV head of the MFMA kernel (the arrival counters of a single-launch call are
+// batch * n_kv_heads * this many)
+int prefix_mfma_query_blocks(const Problem &p);
+hipError_t launch_clear_words(uint32_t *words, int32_t n, hipStream_t stream);
 bool prefix_mfma_supports(const Problem &p, int dtype);
 SplitPlan plan_splits(const ls_desc &d, int32_t n_splits_request);
 hipError_t launch_merge(int32_t batch, int32_t n_q_heads, int32_t n_tree, int32_t head_dim, int dtype,

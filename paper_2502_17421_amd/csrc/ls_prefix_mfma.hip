@@ -60,6 +60,7 @@
 #include <type_traits>
 
 #include "ls_internal.hpp"
+#include "ls_tail.hpp"
 
 
 namespace ls {
@@ -172,7 +173,7 @@ __device__ __forceinline__ int vswz(int row)
 
 template <int D, int NW, bool F16, bool PAGED>
 __global__ void __launch_bounds__(NW * 64, 2048 / (NW * 64) / 4)  // at most 256 registers per lane: no AGPR copies
-prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, int32_t n_qblocks)
+prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, FusedTail tail, int32_t n_qblocks)
 {
     constexpr int KSTEPS = D / 16;            // contraction steps of S^T = K Q^T
     constexpr int MT = D / 32;                // 32-row tiles of O^T along head_dim
@@ -220,6 +221,9 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
     const int g = bz % p.n_kv_heads;
     const int rows_kv = p.group * p.n_tree;
 
+    // The split's own work (a `return` below leaves this block only; in the single-launch call
+    // every wave goes on to the arrival count after it).
+    [&]() __attribute__((always_inline)) {
     int plen = p.prefix_lens ? p.prefix_lens[b] : p.prefix_len_all;
     plen = plen < 0 ? 0 : (plen > p.max_prefix_len ? p.max_prefix_len : plen);
     const int k_lo = split * plan.split_len;
@@ -718,6 +722,44 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, in
             }
     }
     if (lh == 0) out.lse[part_row] = (m_run * c + log2f(l_tot)) * kLn2;
+    }();
+
+    if (tail.arrivals == nullptr) return;
+    // ---- single-launch call: count this workgroup in; the last one of its (sequence, KV head,
+    // query block) merges that block's rows.  The fence makes this workgroup's partial rows
+    // visible to the whole device before its count is; the workgroup that reads the full count
+    // fences again before it reads the others' rows.
+    __threadfence();
+    __syncthreads();  // every wave's rows are out (and nobody uses the staging rows in LDS any more)
+    const int unit = bz * n_qblocks + qblock;
+    volatile uint32_t *seen = (volatile uint32_t *)smem;
+    if (tid == 0)
+        *seen = __hip_atomic_fetch_add(tail.arrivals + unit, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const bool last = __builtin_amdgcn_readfirstlane(*seen) == (uint32_t)plan.n_splits - 1u;
+    if (!last) return;
+    __threadfence();
+    if (tid == 0) __hip_atomic_store(tail.arrivals + unit, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();  // everybody has read the count: LDS is free again
+    // the tree-mask rows of this sequence, in LDS (at most LS_MAX_TREE rows of 8 words: 32 KB)
+    uint64_t *mask_rows = (uint64_t *)smem;
+    build_tree_mask_rows(tail.parents + (size_t)b * p.n_tree, p.n_tree, mask_rows, nullptr, tid, NW * 64);
+    // Four rows per wave and step.  When the block is whole query heads, the four are the same tree
+    // node under four heads, which see the same keys; else consecutive rows.
+    typedef std::conditional_t<F16, half_t, uint16_t> T16;
+    const int row_base = qblock * NW * 32;
+    const int rows_here = rows_kv - row_base < NW * 32 ? rows_kv - row_base : NW * 32;
+    const bool whole_heads = row_base % p.n_tree == 0 && rows_here % p.n_tree == 0;
+    const int heads_here = whole_heads ? rows_here / p.n_tree : 1;
+    for (int step = wave; step * 4 < rows_here; step += NW) {
+        int k = step * 4 + (lane >> 4);
+        const bool live = k < rows_here;
+        k = live ? k : rows_here - 1;
+        const int m = whole_heads ? row_base + (k % heads_here) * p.n_tree + k / heads_here : row_base + k;
+        tail_rows<T16, T16, D, 16, 8>(p, mask_rows, out, plan.n_splits, (T16 *)tail.out, tail.o_stride[0],
+                                      tail.o_stride[1], tail.o_stride[2], tail.lse, b, g * p.group + m / p.n_tree,
+                                      m % p.n_tree, live, lane);
+    }
 }
 
 bool prefix_mfma_supports(const Problem &p, int dtype)
@@ -731,7 +773,7 @@ namespace {
 
 template <int D, int NW, bool F16, bool PAGED>
 hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
-                      hipStream_t stream)
+                      const FusedTail &tail, hipStream_t stream)
 {
     constexpr int lds_bytes = (KS + VS) * TK * D * 2 + (PAGED ? kMaxSplitPages * 4 : 0);
     static_assert(lds_bytes <= 160 * 1024, "the rings exceed the 160 KB of a compute unit");
@@ -745,15 +787,24 @@ hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &o
     const int64_t n_main = (int64_t)plan.n_splits * n_qblocks * p.batch * p.n_kv_heads;
     const int64_t n_blocks = n_main + (mask_job.parents ? p.batch : 0);
     if (n_blocks > 0x7fffffff) return hipErrorInvalidValue;
+    if (tail.arrivals && (!out.o_is_16bit || (int64_t)n_qblocks * p.batch * p.n_kv_heads > kMaxArrivalCounters))
+        return hipErrorInvalidValue;
     hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), lds_bytes, stream, p, plan, out, mask_job,
-                       n_qblocks);
+                       tail, n_qblocks);
     return hipGetLastError();
 }
 
 }  // namespace
 
+int prefix_mfma_query_blocks(const Problem &p)
+{
+    const int rows_kv = p.group * p.n_tree;
+    const int per_block = rows_kv > 128 ? 256 : 128;
+    return (rows_kv + per_block - 1) / per_block;
+}
+
 hipError_t launch_prefix_mfma(const Problem &p, int dtype, const SplitPlan &plan, const Partials &out,
-                              const MaskJob &mask_job, hipStream_t stream)
+                              const MaskJob &mask_job, const FusedTail &tail, hipStream_t stream)
 {
     const int rows_kv = p.group * p.n_tree;
     const bool f16 = dtype == LS_F16;
@@ -761,10 +812,10 @@ hipError_t launch_prefix_mfma(const Problem &p, int dtype, const SplitPlan &plan
     // Above 128 query rows per KV head: 8 waves, two per SIMD, 256 rows per workgroup (the split
     // planner counts on kPrefixRowsPerWorkgroup = 256); else 4 waves.
 #define LS_MFMA_CASE2(DD, WW)                                                                     \
-    (paged ? (f16 ? launch_one<DD, WW, true, true>(p, plan, out, mask_job, stream)               \
-                  : launch_one<DD, WW, false, true>(p, plan, out, mask_job, stream))             \
-           : (f16 ? launch_one<DD, WW, true, false>(p, plan, out, mask_job, stream)              \
-                  : launch_one<DD, WW, false, false>(p, plan, out, mask_job, stream)))
+    (paged ? (f16 ? launch_one<DD, WW, true, true>(p, plan, out, mask_job, tail, stream)               \
+                  : launch_one<DD, WW, false, true>(p, plan, out, mask_job, tail, stream))             \
+           : (f16 ? launch_one<DD, WW, true, false>(p, plan, out, mask_job, tail, stream)              \
+                  : launch_one<DD, WW, false, false>(p, plan, out, mask_job, tail, stream)))
 #define LS_MFMA_CASE(DD) (rows_kv > 128 ? LS_MFMA_CASE2(DD, 8) : LS_MFMA_CASE2(DD, 4))
     if (p.head_dim == 128) return LS_MFMA_CASE(128);
     if (p.head_dim == 64) return LS_MFMA_CASE(64);

@@ -69,3 +69,13 @@ class DeviceBatch:
         ls.ls_hybrid_tree_attn(self.desc, self.q, self.k_cache, self.v_cache, self.prefix_lens, self.k_tree,
                                self.v_tree, self.parents, self.out, self.lse, self.workspace, stream=stream)
         return self.out, self.lse
+
+    def run_fused(self, stream=None):
+        """The single-launch form; the workspace's arrival counters are zeroed when it is created."""
+        if self.workspace is None:
+            n = ls.ls_workspace_bytes(self.desc)
+            self.workspace = torch.full((n,), 0xFF, dtype=torch.uint8, device=self.q.device)
+            ls.ls_workspace_init(self.workspace, stream=stream)
+        ls.ls_hybrid_tree_attn_fused(self.desc, self.q, self.k_cache, self.v_cache, self.prefix_lens, self.k_tree,
+                                     self.v_tree, self.parents, self.out, self.lse, self.workspace, stream=stream)
+        return self.out, self.lse

@@ -161,11 +161,13 @@ def test_validate_parents_host():
 
 
 def even_cut_bytes(d, e=2):
-    """Workspace size when every query block is cut into ls_prefix_num_splits pieces."""
+    """Workspace size when every query block is cut into ls_prefix_num_splits pieces (the arrival
+    counters of the single-launch call come first, at a size that no descriptor changes)."""
     up = lambda n: (n + 255) // 256 * 256
     rows = d.batch * d.n_q_heads * ls.ls_prefix_num_splits(d) * d.n_tree
     words = (d.n_tree + 63) // 64
-    return up(d.batch * d.n_tree * words * 8) + up(d.batch * 4) + up(rows * 4) + up(rows * d.head_dim * e)
+    return (ls.LS_WORKSPACE_COUNTER_BYTES + up(d.batch * d.n_tree * words * 8) + up(d.batch * 4) + up(rows * 4) +
+            up(rows * d.head_dim * e))
 
 
 def test_workspace_follows_the_schedule_of_the_whole_call():

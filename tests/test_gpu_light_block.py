@@ -37,7 +37,8 @@ def uniform_workspace_bytes(db, w):
     rows = w.batch * w.n_q_heads * s * w.n_tree
     words = (w.n_tree + 63) // 64
     e = 4 if w.dtype == "f32" else 2
-    return up(w.batch * w.n_tree * words * 8) + up(w.batch * 4) + up(rows * 4) + up(rows * w.head_dim * e)
+    return (ls.LS_WORKSPACE_COUNTER_BYTES + up(w.batch * w.n_tree * words * 8) + up(w.batch * 4) + up(rows * 4) +
+            up(rows * w.head_dim * e))
 
 
 CASES = [
