@@ -202,13 +202,19 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
     }
     plan.n_splits = (int32_t)s;
     plan.split_len = (int32_t)len;
-    plan.rem_splits = 0;
-    plan.rem_split_len = 0;
+    plan.per_sequence = 0;
+    plan.reserved = 0;
     return plan;
 }
 
-// Schedule of the whole-path calls: the same as the stand-alone cached-key call.
-SplitPlan plan_call(const ls_desc &d) { return plan_splits(d, 0); }
+// Schedule of the whole-path calls: as many pieces as the stand-alone cached-key call would cut,
+// but on the MFMA path every sequence cuts its own length into that many (SplitPlan::per_sequence).
+SplitPlan plan_call(const ls_desc &d)
+{
+    SplitPlan plan = plan_splits(d, 0);
+    plan.per_sequence = is_16bit(d.dtype) ? 1 : 0;
+    return plan;
+}
 
 }  // namespace ls
 

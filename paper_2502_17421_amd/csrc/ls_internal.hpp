@@ -81,12 +81,12 @@ constexpr int kMaxArrivalCounters = 4096;  // (sequence, KV head, query block) t
 struct SplitPlan {
     int32_t n_splits;   // parts the cached-key kernel writes
     int32_t split_len;  // cache rows per split
-    // MFMA path, whole-path calls only: when the last query block of a KV head holds few rows,
-    // its workgroups run faster per key tile than the full ones, and the keys are cut into
-    // fewer, longer pieces for it (rem_splits <= n_splits pieces of rem_split_len rows; 0: the
-    // last query block is cut like the others).  Its parts [rem_splits, n_splits) are empty.
-    int32_t rem_splits;
-    int32_t rem_split_len;
+    // MFMA path, whole-path calls only (their parts are nobody else's business): every sequence
+    // cuts ITS cached rows into n_splits equal pieces (a multiple of 32 rows, at most split_len)
+    // instead of pieces of split_len rows sized for the longest sequence the cache can hold, so
+    // that a short sequence keeps as many workgroups busy as a long one.
+    int32_t per_sequence;
+    int32_t reserved;
 };
 
 // bf16 <-> float on raw 16-bit patterns (round to nearest even, NaN kept quiet).

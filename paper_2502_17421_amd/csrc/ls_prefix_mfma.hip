@@ -226,8 +226,10 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
     [&]() __attribute__((always_inline)) {
     int plen = p.prefix_lens ? p.prefix_lens[b] : p.prefix_len_all;
     plen = plen < 0 ? 0 : (plen > p.max_prefix_len ? p.max_prefix_len : plen);
-    const int k_lo = split * plan.split_len;
-    int k_hi = k_lo + plan.split_len;
+    int split_len = plan.split_len;
+    if (plan.per_sequence) split_len = ((plen + plan.n_splits - 1) / plan.n_splits + TK - 1) / TK * TK;
+    const int k_lo = split * split_len;
+    int k_hi = k_lo + split_len;
     k_hi = k_hi > plen ? plen : k_hi;
 
     // The query row of this lane.
@@ -783,7 +785,6 @@ hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &o
     if (attr != hipSuccess) return attr;
     const int rows_kv = p.group * p.n_tree;
     const int n_qblocks = (rows_kv + NW * 32 - 1) / (NW * 32);
-    if (plan.rem_splits != 0) return hipErrorInvalidValue;
     const int64_t n_main = (int64_t)plan.n_splits * n_qblocks * p.batch * p.n_kv_heads;
     const int64_t n_blocks = n_main + (mask_job.parents ? p.batch : 0);
     if (n_blocks > 0x7fffffff) return hipErrorInvalidValue;
