@@ -12,7 +12,7 @@ namespace ls {
 constexpr int kWave = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kMaxSplitPages = 512;  // pages one key split of the MFMA kernel may touch (page ids sit in 8 registers)
+constexpr int kMaxSplitPages = 512;  // pages one key split of the MFMA kernel may touch (their ids sit in 2 KB of LDS)
 constexpr int kPrefixRowsPerWorkgroup = 256;  // query rows per workgroup of the MFMA kernel (8 waves x 32 rows)
 constexpr int kPrefixWorkgroupsPerCU = 1;     // workgroups resident per compute unit
 constexpr int kMaxSplitLen = 8192;    // cache rows per split on the MFMA path: 512 pages of the smallest page size, 16

@@ -26,7 +26,8 @@
 //
 // Paged caches: a load instruction covers 4 or 8 consecutive rows, which a page of 16 rows
 // or more never splits, so each instruction takes the base of its own page; the page ids of
-// the split sit in registers (one lane per page) and are picked with v_readlane.
+// the split are read once into LDS behind the rings, and a tile request picks its pages from
+// there.
 //
 // The partial outputs leave through LDS (free by then) as whole 16-byte-per-lane rows with
 // streaming stores; stored straight from the accumulator layout every store would touch 32
