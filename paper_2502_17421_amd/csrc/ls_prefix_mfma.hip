@@ -597,10 +597,41 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
         if (h + PD < n_tiles) wait_vmem<(PD - 2) * INFLIGHT>();
         else wait_vmem<0>();
         ring_barrier();
-        request_k();
-        request_v();
-        request_k();
-        request_v();
+        if (!loader) return;  // wave-uniform: the other waves keep no request state
+        // The four requests touch three consecutive tiles (V of t0, K and V of t1, K of t2).  When
+        // all three exist, are whole and lie side by side in the cache (no wrap of the tile order),
+        // the copies need no checks: one straight run of eight copy instructions per tensor pair.
+        bool fast = false;
+        if constexpr (!PAGED) fast = rq_kt + 1 < n_tiles && rq_v0 + 3 * TK <= k_hi;
+        if (fast) {
+            // K of t1, V of t0, K of t2, V of t1: the order of the general path
+            auto run = [&](const uint8_t *base, const uint32_t (&voff)[LOADS], uint32_t dst) __attribute__((always_inline)) {
+                const uint32_t d0 = __builtin_amdgcn_readfirstlane(smem_off + dst);
+#pragma unroll
+                for (int j = 0; j < LOADS; ++j) copy_to_lds(base, voff[j], d0 + load_row0(j) * ROWB);
+            };
+            run(rq_kptr, k_voff, rq_koff);
+            rq_koff = next_k(rq_koff);
+            run(rq_vptr, v_voff, rq_voff);
+            rq_voff = next_v(rq_voff);
+            rq_kptr += TK * k_row_bytes;
+            rq_vptr += TK * v_row_bytes;
+            run(rq_kptr, k_voff, rq_koff);
+            rq_koff = next_k(rq_koff);
+            run(rq_vptr, v_voff, rq_voff);
+            rq_voff = next_v(rq_voff);
+            rq_kt += 2;
+            rq_vt += 2;
+            rq_v0 += 2 * TK;                  // = the old t2: still inside the split
+            rq_vptr += TK * v_row_bytes;
+            rq_k0 = next_key0(rq_v0);         // the tile after t2 may be where the order wraps
+            rq_kptr = rq_k0 == k_lo ? k_ptr_lo : rq_kptr + TK * k_row_bytes;
+        } else {
+            request_k();
+            request_v();
+            request_k();
+            request_v();
+        }
     };
     // A wave whose rows all lie past the last query row of the KV head (the last query block of a
     // head whose row count is not a multiple of the block) only keeps feeding the rings: its
