@@ -206,9 +206,10 @@ int ls_hybrid_tree_attn_static(const ls_desc *desc, const void *q,
  *   - Problems outside the matrix-core kernel (float inputs, row strides beyond its reach) or
  *     with more than 4096 (sequence, KV head, query block) triples run as
  *     ls_hybrid_tree_attn does, in two launches.
- *   - Which form is faster depends on the shape: the merging workgroups work alone while the
- *     rest of the chip has finished or is still busy with other blocks.  Measured figures are
- *     in the design notes; ls_hybrid_tree_attn is the default.
+ *   - The merging workgroup of a query block works alone, after every other workgroup of that
+ *     block has finished: on MI355X this form was slower than the two launches of
+ *     ls_hybrid_tree_attn on every shape measured (3x at the 32k-key, 64-node benchmark shape).
+ *     It is for callers that must have a single launch; ls_hybrid_tree_attn is the default.
  */
 #define LS_WORKSPACE_COUNTER_BYTES (4096u * 4u)
 int ls_workspace_init(void *workspace /* DEVICE, 256-byte aligned */, size_t workspace_bytes, void *stream);
