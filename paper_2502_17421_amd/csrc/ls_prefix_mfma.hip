@@ -15,8 +15,8 @@
 // their own, because a tile's V rows are read two pipeline steps after its K rows: they are
 // requested one step later than its K rows, and still arrive a step earlier than needed.  With
 // PD requests in flight, issued two at a time (one workgroup barrier per two tiles), the K ring
-// has PD + 3 stages and the V ring PD + 4 (PD = 6: 152 KB at head_dim 128): what a compute unit
-// has in flight is what hides the HBM latency.  The instruction writes LDS
+// has PD + 3 stages and the V ring PD + 4 (PD = 6: 152 KB at head_dim 128; PD = 3: 104 KB): what a
+// compute unit has in flight is what hides the HBM latency.  The instruction writes LDS
 // linearly (lane l -> base + 16*l), so the bank swizzle is applied on the global side:
 // the lane that fills LDS slot (row, pos) fetches chunk pos ^ swizzle(row) of that row.
 //
@@ -77,9 +77,14 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TK = 32;              // keys per tile = keys per pipeline step (one MFMA row tile)
-constexpr int PD = 6;               // requests (a K tile and a V tile each) in flight
-constexpr int KS = PD + 3;          // stages of the K ring
-constexpr int VS = PD + 4;          // stages of the V ring
+// PD, a template parameter of the kernel: requests (a K tile and a V tile each) in flight.  The K
+// ring has PD + 3 stages, the V ring PD + 4.  Short splits take PD = 6: nearly all their tiles are
+// requested at once and arrive while the first ones are worked on.  Long splits take PD = 3: a
+// compute unit's share of the HBM stream fills a window of 13 tiles in about 6 us, during which
+// nothing is computed, and three requests in flight are as many as the memory pipeline of a
+// compute unit holds anyway.
+constexpr int kDeepRequests = 6, kShallowRequests = 3;
+constexpr int kDeepMaxTiles = 16;   // splits of at most this many tiles take the deep window
 constexpr float kLazy = 8.f;        // general path: m is raised only when a score exceeds it by 2^8
 // common path: largest row-sum increment taken without raising m; the numerators are stored in
 // the operand type, and a half holds nothing above 65504
@@ -172,10 +177,12 @@ __device__ __forceinline__ int vswz(int row)
 
 }  // namespace
 
-template <int D, int NW, bool F16, bool PAGED>
+template <int D, int NW, bool F16, bool PAGED, int PD>
 __global__ void __launch_bounds__(NW * 64, 2048 / (NW * 64) / 4)  // at most 256 registers per lane: no AGPR copies
 prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, FusedTail tail, int32_t n_qblocks)
 {
+    constexpr int KS = PD + 3;                // stages of the K ring
+    constexpr int VS = PD + 4;                // stages of the V ring
     constexpr int KSTEPS = D / 16;            // contraction steps of S^T = K Q^T
     constexpr int MT = D / 32;                // 32-row tiles of O^T along head_dim
     constexpr int CH = D / 8;                 // 16-byte chunks per K/V row
@@ -805,13 +812,13 @@ bool prefix_mfma_supports(const Problem &p, int dtype)
 
 namespace {
 
-template <int D, int NW, bool F16, bool PAGED>
+template <int D, int NW, bool F16, bool PAGED, int PD>
 hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &out, const MaskJob &mask_job,
                       const FusedTail &tail, hipStream_t stream)
 {
-    constexpr int lds_bytes = (KS + VS) * TK * D * 2 + (PAGED ? kMaxSplitPages * 4 : 0);
+    constexpr int lds_bytes = (2 * PD + 7) * TK * D * 2 + (PAGED ? kMaxSplitPages * 4 : 0);
     static_assert(lds_bytes <= 160 * 1024, "the rings exceed the 160 KB of a compute unit");
-    auto kernel = prefix_mfma_kernel<D, NW, F16, PAGED>;
+    auto kernel = prefix_mfma_kernel<D, NW, F16, PAGED, PD>;
     static hipError_t attr = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  lds_bytes);
     if (attr != hipSuccess) return attr;
@@ -844,16 +851,19 @@ hipError_t launch_prefix_mfma(const Problem &p, int dtype, const SplitPlan &plan
     const bool paged = p.block_table != nullptr;
     // Above 128 query rows per KV head: 8 waves, two per SIMD, 256 rows per workgroup (the split
     // planner counts on kPrefixRowsPerWorkgroup = 256); else 4 waves.
-#define LS_MFMA_CASE2(DD, WW)                                                                     \
-    (paged ? (f16 ? launch_one<DD, WW, true, true>(p, plan, out, mask_job, tail, stream)               \
-                  : launch_one<DD, WW, false, true>(p, plan, out, mask_job, tail, stream))             \
-           : (f16 ? launch_one<DD, WW, true, false>(p, plan, out, mask_job, tail, stream)              \
-                  : launch_one<DD, WW, false, false>(p, plan, out, mask_job, tail, stream)))
+    const bool deep = plan.split_len <= kDeepMaxTiles * TK;  // few tiles per split: request them all at once
+#define LS_MFMA_CASE3(DD, WW, PP)                                                                      \
+    (paged ? (f16 ? launch_one<DD, WW, true, true, PP>(p, plan, out, mask_job, tail, stream)           \
+                  : launch_one<DD, WW, false, true, PP>(p, plan, out, mask_job, tail, stream))         \
+           : (f16 ? launch_one<DD, WW, true, false, PP>(p, plan, out, mask_job, tail, stream)          \
+                  : launch_one<DD, WW, false, false, PP>(p, plan, out, mask_job, tail, stream)))
+#define LS_MFMA_CASE2(DD, WW) (deep ? LS_MFMA_CASE3(DD, WW, kDeepRequests) : LS_MFMA_CASE3(DD, WW, kShallowRequests))
 #define LS_MFMA_CASE(DD) (rows_kv > 128 ? LS_MFMA_CASE2(DD, 8) : LS_MFMA_CASE2(DD, 4))
     if (p.head_dim == 128) return LS_MFMA_CASE(128);
     if (p.head_dim == 64) return LS_MFMA_CASE(64);
 #undef LS_MFMA_CASE
 #undef LS_MFMA_CASE2
+#undef LS_MFMA_CASE3
     return hipErrorInvalidValue;
 }
 
