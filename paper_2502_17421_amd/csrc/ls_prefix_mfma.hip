@@ -273,7 +273,11 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
     // The rows a loader wave copies: LOADS groups of ROWS_PER_LOAD rows per tensor, group j starting
     // at tile row load_row0(j).
     const bool loader = wave < NL;
-    auto load_row0 = [&](int j) __attribute__((always_inline)) { return (wave * LOADS + j) * ROWS_PER_LOAD; };
+    // With eight waves, the first window of tiles (requests -PD .. -1) is copied by the other four:
+    // a wave that issues a whole window sits in the issue stall while the window fills, and the
+    // loader waves should be through tile 0 by then.  Wave NL + i copies the rows loader i would.
+    const bool starter = NW >= 2 * NL ? (wave >= NL && wave < 2 * NL) : loader;
+    auto load_row0 = [&](int j) __attribute__((always_inline)) { return ((wave % NL) * LOADS + j) * ROWS_PER_LOAD; };
     // byte offsets of this lane's pieces relative to the first row of a tile (whole tiles)
     uint32_t k_voff[LOADS], v_voff[LOADS];
 #pragma unroll
@@ -304,9 +308,9 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
     // the end of the split repeat its last row; their scores are masked.
     // Paged: one load instruction covers ROWS_PER_LOAD consecutive rows, which never straddle a
     // page (page sizes are powers of two >= 16): its base is that of its own page.
-    auto issue_rows = [&](auto is_v_tag, int k0, const uint8_t *tile_base, uint32_t dst) __attribute__((always_inline)) {
+    auto issue_rows = [&](auto is_v_tag, int k0, const uint8_t *tile_base, uint32_t dst, bool mine) __attribute__((always_inline)) {
         constexpr bool IS_V = decltype(is_v_tag)::value;
-        if (!loader) return;  // wave-uniform
+        if (!mine) return;  // wave-uniform
         const uint32_t d0 = __builtin_amdgcn_readfirstlane(smem_off + dst);
         const int last = k_hi - 1 - k0;  // last valid row of the tile (>= TK - 1 for whole tiles)
         const int64_t row_bytes = IS_V ? v_row_bytes : k_row_bytes;
@@ -369,30 +373,33 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
     int rq_kt = 0, rq_k0 = key_first, rq_vt = 0, rq_v0 = key_first;
     const uint8_t *rq_kptr = uniform_ptr(kbase + key_first * k_row_bytes), *rq_vptr = uniform_ptr(vbase + key_first * v_row_bytes);
     uint32_t rq_koff = 0, rq_voff = V_RING;
-    auto request_k = [&]() __attribute__((always_inline)) {
-        if (rq_kt < n_tiles) issue_rows(is_k{}, rq_k0, rq_kptr, rq_koff);
+    // (mine: this wave is among those that copy this request; every wave keeps the state)
+    auto request_k = [&](bool mine) __attribute__((always_inline)) {
+        if (rq_kt < n_tiles) issue_rows(is_k{}, rq_k0, rq_kptr, rq_koff, mine);
         ++rq_kt;
         rq_k0 = next_key0(rq_k0);
         rq_kptr = rq_k0 == k_lo ? k_ptr_lo : rq_kptr + TK * k_row_bytes;
         rq_koff = next_k(rq_koff);
     };
-    auto request_v = [&]() __attribute__((always_inline)) {
-        if (rq_vt < n_tiles) issue_rows(is_v{}, rq_v0, rq_vptr, rq_voff);
+    auto request_v = [&](bool mine) __attribute__((always_inline)) {
+        if (rq_vt < n_tiles) issue_rows(is_v{}, rq_v0, rq_vptr, rq_voff, mine);
         ++rq_vt;
         rq_v0 = next_key0(rq_v0);
         rq_vptr = rq_v0 == k_lo ? v_ptr_lo : rq_vptr + TK * v_row_bytes;
         rq_voff = next_v(rq_voff);
     };
-    request_k();  // request -(PD+1)
+    request_k(loader);  // request -(PD+1)
 #pragma unroll
     for (int r = -PD; r < 0; ++r) {
-        request_k();
-        request_v();
+        request_k(starter);
+        request_v(starter);
     }
 
     // Collect Q and the K rows of tile 0: everything older than requests -PD .. -1 has landed.
     // (A wave that copies nothing has only its Q loads outstanding.)
-    if (loader && n_tiles > PD) wait_vmem<PD * INFLIGHT>();
+    // (With eight waves a loader has only Q and tile 0 outstanding and waits for all of it; a
+    // starter has its Q loads in front of its PD requests.)
+    if (starter && n_tiles > PD) wait_vmem<PD * INFLIGHT>();
     else wait_vmem<0>();  // short split: its requests are not all whole; wait for everything
     bf16x8 q_reg[KSTEPS];
 #pragma unroll
@@ -592,17 +599,25 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
             if (n_tiles > PD) wait_vmem<(PD - 1) * INFLIGHT>();
             else wait_vmem<0>();
             ring_barrier();
-            request_k();
-            request_v();
+            request_k(loader);
+            request_v(loader);
         }
     };
     // Before half-steps h and h+1 (h odd), which read K rows up to tile h+2: requests up to h+1-PD
     // have landed; requests h and h+1 follow, into stages last read in half-step h-1 or earlier.
     // Near the end of the split the outstanding requests are not whole any more, and the wave
     // waits for everything.
+    // A starter that is not a loader has nothing but the first window outstanding: before pair 1
+    // its requests up to 2 - PD have landed, from pair 3 on all of them.
     auto advance_pair = [&](int h) __attribute__((always_inline)) {
-        if (h + PD < n_tiles) wait_vmem<(PD - 2) * INFLIGHT>();
-        else wait_vmem<0>();
+        if (starter && !loader) {
+            if (h == 1 && 1 + PD < n_tiles) wait_vmem<(PD > 3 ? PD - 3 : 0) * INFLIGHT>();
+            else wait_vmem<0>();
+        } else if (h + PD < n_tiles) {
+            wait_vmem<(PD - 2) * INFLIGHT>();
+        } else {
+            wait_vmem<0>();
+        }
         ring_barrier();
         if (!loader) return;  // wave-uniform: the other waves keep no request state
         // The four requests touch three consecutive tiles (V of t0, K and V of t1, K of t2).  When
@@ -634,10 +649,10 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
             rq_k0 = next_key0(rq_v0);         // the tile after t2 may be where the order wraps
             rq_kptr = rq_k0 == k_lo ? k_ptr_lo : rq_kptr + TK * k_row_bytes;
         } else {
-            request_k();
-            request_v();
-            request_k();
-            request_v();
+            request_k(true);
+            request_v(true);
+            request_k(true);
+            request_v(true);
         }
     };
     // A wave whose rows all lie past the last query row of the KV head (the last query block of a
