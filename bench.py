@@ -220,6 +220,7 @@ def main():
     probe = ctypes.CDLL(ls_build.PROBE_LIB_PATH)   # measurement helpers, a library of their own
     probe.ls_probe_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
     probe.ls_probe_mfma_loop.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
+    probe.ls_probe_mfma_loop_varied.argtypes = probe.ls_probe_mfma_loop.argtypes
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
@@ -423,8 +424,25 @@ def main():
     p1.record(stream)
     torch.cuda.synchronize()
     mfma_sustained = (n_sus // 5) * mf / (p0.elapsed_time(p1) * 1e-3) / 1e12
+    # and on operands that vary from lane to lane and instruction to instruction, as real keys
+    # and values do (constant operands draw far less power): sustained rate again
+    def mfma_loop_varied(iters):
+        fl_out = ctypes.c_int64(0)
+        assert probe.ls_probe_mfma_loop_varied(iters, ctypes.c_void_p(sink.data_ptr()), ctypes.byref(fl_out),
+                                               raw_stream) == 0
+        return int(fl_out.value)
+
+    for _ in range(n_sus - n_sus // 5):
+        mfma_loop_varied(20000)
+    p0.record(stream)
+    for _ in range(n_sus // 5):
+        mf = mfma_loop_varied(20000)
+    p1.record(stream)
+    torch.cuda.synchronize()
+    mfma_varied = (n_sus // 5) * mf / (p0.elapsed_time(p1) * 1e-3) / 1e12
     practical = {"stream_read_gbs": read_gbs, "mfma_bf16_issue_loop_tflops": mfma_tflops,
-                 "mfma_bf16_issue_loop_sustained_tflops": mfma_sustained}
+                 "mfma_bf16_issue_loop_sustained_tflops": mfma_sustained,
+                 "mfma_bf16_issue_loop_varied_operands_sustained_tflops": mfma_varied}
 
     bytes_prefix = algorithmic_bytes_prefix(w, plens)
     bytes_call = algorithmic_bytes_call(w, plens)

@@ -46,6 +46,49 @@ __global__ void __launch_bounds__(512) mfma_loop_kernel(int iters, float *sink)
     if (s == 12345.f) sink[0] = s;
 }
 
+// The same loop on operands that differ from lane to lane and from one instruction to the next
+// (hashed sign and mantissa bits, magnitudes in [1, 2)): what the matrix cores sustain when their
+// inputs toggle as real keys and values do.  With constant operands the loop above draws far less
+// power and holds a higher clock.
+__device__ inline uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+__global__ void __launch_bounds__(512) mfma_loop_varied_kernel(int iters, float *sink)
+{
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint16_t av[8], bv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t h = mix32((threadIdx.x * 4u + k) * 8u + e + 0x9e3779b9u * (blockIdx.x + 1u));
+            av[e] = (uint16_t)(0x3f80u | (h & 0x807fu));          // +-[1, 2)
+            bv[e] = (uint16_t)(0x3f80u | ((h >> 16) & 0x807fu));
+        }
+        __builtin_memcpy(&a[k], av, 16);
+        __builtin_memcpy(&b[k], bv, 16);
+    }
+    floatx16 c[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[k][r] = 0.f;
+    for (int i = 0; i < iters; i += 4)  // iters is a multiple of 4
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                c[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[k], b[(k + r) & 3], c[k], 0, 0, 0);
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += c[k][r];
+    if (s == 12345.f) sink[0] = s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -71,6 +114,18 @@ int ls_probe_mfma_loop(int32_t iters, void *sink, int64_t *flops_out, void *stre
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     hipLaunchKernelGGL(mfma_loop_kernel, dim3(cus), dim3(512), 0, (hipStream_t)stream, iters, (float *)sink);
     // 8 waves x 4 chains x one 32x32x16 MFMA (2*32*32*16 flop) per iteration and workgroup
+    if (flops_out) *flops_out = (int64_t)8 * 4 * 2 * 32 * 32 * 16 * iters * cus;
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// The same launch shape and flop count with operands that vary per lane and per instruction;
+// iters must be a multiple of 4.
+int ls_probe_mfma_loop_varied(int32_t iters, void *sink, int64_t *flops_out, void *stream)
+{
+    if (!sink || iters <= 0 || iters > (1 << 24) || iters % 4) return -1;
+    int cus = 256, dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    hipLaunchKernelGGL(mfma_loop_varied_kernel, dim3(cus), dim3(512), 0, (hipStream_t)stream, iters, (float *)sink);
     if (flops_out) *flops_out = (int64_t)8 * 4 * 2 * 32 * 32 * 16 * iters * cus;
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
