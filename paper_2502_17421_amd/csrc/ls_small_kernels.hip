@@ -230,10 +230,13 @@ hipError_t launch_merge(int32_t batch, int32_t n_q_heads, int32_t n_tree, int32_
 constexpr int kTailWideMaxRows = 8192;
 
 // Waves per SIMD the compiler must leave room for (every load carries a 64-bit address of its
-// own, so the register count is well above that of the data in flight).
+// own, so the register count is well above that of the data in flight).  The form for many rows
+// (16 lanes per row, four 16-bit split rows per request) fits three; calls with tens of thousands of
+// rows run in rounds of resident wavefronts, and a third wavefront per SIMD shortens them more
+// than the registers it gives up would.
 template <int LPR, int CH, int PART_BYTES> constexpr int tail_waves_per_simd()
 {
-    return (LPR == 16 && CH == 16) || CH * PART_BYTES >= 256 ? 1 : 2;
+    return (LPR == 16 && CH == 16) || CH * PART_BYTES >= 256 ? 1 : (LPR == 16 && CH * PART_BYTES < 128 ? 3 : 2);
 }
 
 template <typename T, typename PT, int D, int LPR, int CH>
@@ -274,8 +277,7 @@ hipError_t launch_tree_merge(const Problem &p, int dtype, const uint64_t *mask, 
 #define LS_TM_CASE(T, PT, DD)                                        \
     do {                                                             \
         if (wide) LS_TM_LAUNCH(T, PT, DD, 64, 32);                   \
-        else if (n_cache_parts <= 4) LS_TM_LAUNCH(T, PT, DD, 16, 4); \
-        else if (n_cache_parts <= 8) LS_TM_LAUNCH(T, PT, DD, 16, 8); \
+        else if (n_cache_parts <= 8) LS_TM_LAUNCH(T, PT, DD, 16, 4); \
         else LS_TM_LAUNCH(T, PT, DD, 16, 16);                        \
     } while (0)
     if (p.head_dim != 64 && p.head_dim != 128) return hipErrorInvalidValue;

@@ -177,10 +177,13 @@ __device__ __forceinline__ void tail_rows(const Problem &p, const uint64_t *mask
     typedef Lanes<T, EPL> LT;
     typedef Lanes<PT, EPL> LP;
     constexpr int QB = LT::BYTES, PB = LP::BYTES;
-    constexpr int KB = QB > 16 ? 2 : 4;  // tree keys per request (K and V rows); two requests in flight
+    // Tree keys per request (K and V rows); two requests are in flight.  With 16 lanes per row a
+    // key costs eight registers, and two keys per request keep the wavefront small enough for
+    // three or four of them per SIMD, which hides more latency than longer requests do.
+    constexpr int KB = LPR == 16 || QB > 16 ? 2 : 4;
     // CH: split rows requested together, at most LPR (their weights come from the lanes of the
-    // row).  LPR = 16, CH = 16 keeps two such requests in flight (32 split rows); the forms with
-    // CH < 16 are for at most CH parts; LPR = 64 has CH = 32.
+    // row).  LPR = 16, CH = 16 keeps two such requests in flight (32 split rows); CH = 4 serves
+    // rows of at most 8 parts (one or two requests, one after the other); LPR = 64 has CH = 32.
     static_assert(CH <= LPR && (LPR == 16 || LPR == 64), "");
     constexpr bool TWO_SETS = LPR == 16 && CH == 16 && 2 * CH * PB <= 512;
     const int sl = lane & (LPR - 1);

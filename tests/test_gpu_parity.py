@@ -265,6 +265,8 @@ def test_full_path_other_shapes(dtype, hq, hkv, d, t, plens):
     ("bf16", 3, 3, 128, 7, 3, [5000]),        # 21 rows: the last wavefront is part empty; no query grouping
     ("bf16", 10, 2, 128, 300, 40, [1500]),    # five mask words, up to 41 visible keys per row, group of five
     ("bf16", 40, 8, 128, 33, 8, [900, 40]),   # at most four parts, 16 lanes per row
+    ("bf16", 40, 8, 128, 33, 8, [2000, 700]), # five to eight parts: two requests of four, one after the other
+    ("f16", 20, 4, 64, 130, 9, [1800]),       # the same with head_dim 64 and three mask words
     ("f32", 4, 2, 128, 70, 12, [3000]),       # float rows of 512 bytes, two mask words
 ])
 def test_tail_kernel_forms(dtype, hq, hkv, d, t, depth, plens):
