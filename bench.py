@@ -188,7 +188,7 @@ def main():
     ap.add_argument("--page-size", type=int, default=0,
                     help="keep the cache in shuffled pages of this many rows and call ls_hybrid_tree_attn_paged")
     ap.add_argument("--single-launch", action="store_true",
-                    help="time ls_hybrid_tree_attn_fused (the last workgroup of each query block merges) instead "
+                    help="time ls_hybrid_tree_attn_fused (the workgroups of a query block share its merge) instead "
                          "of the two-launch call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hot", action="store_true", help="skip the timing with one K/V copy (cache-resident)")

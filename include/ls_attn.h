@@ -188,36 +188,45 @@ int ls_hybrid_tree_attn_static(const ls_desc *desc, const void *q,
 
 /*
  * The whole call as ONE kernel launch (Section 3.3: the two attention results are aggregated;
- * here the aggregation runs inside the kernel that computes the cached-key part).  Every
- * workgroup of the cached-key kernel, once its partial rows are written and fenced, adds one
- * to a counter of its (sequence, KV head, query block); the workgroup that finds all the
- * others already counted builds the tree mask, does the masked tree attention and merges, in
- * fixed part order, for that block's rows.  Nothing waits for anything (no wait can fail to
- * end), and the result does not depend on which workgroup arrives last: the same inputs give
- * bit-identical outputs.  The results agree with ls_hybrid_tree_attn to rounding (the row sums
- * are taken in another lane order), not bit for bit.
+ * here the aggregation runs inside the kernel that computes the cached-key part).  The
+ * workgroups of one (sequence, KV head, query block), one per key split, count themselves in
+ * once their partial rows are written and fenced.  When every workgroup of the launch has a
+ * compute unit to itself from the start (their number is at most the device's compute units),
+ * each then waits, a bounded number of polls, for the count of its block to complete, and
+ * does the tree mask, the masked tree attention and the merge, in fixed part order, for its
+ * share of the block's rows; the workgroup that completed the count also takes the rows of any
+ * workgroup that gave up waiting.  In larger launches nobody waits and the workgroup that
+ * completes a block's count does all of that block's rows.  Every row is written once, by the
+ * same code whoever writes it: the same inputs give bit-identical outputs.  The results agree
+ * with ls_hybrid_tree_attn to rounding (the row sums are taken in another lane order), not bit
+ * for bit.
  *
  *   - Arguments, workspace size and error words as for ls_hybrid_tree_attn.
  *   - The counters are the first LS_WORKSPACE_COUNTER_BYTES of the workspace, whatever the
- *     descriptor.  They must be zero when the call starts and are zero again when it ends:
- *     call ls_workspace_init once on a fresh workspace (and again after anything else wrote
- *     there).  ls_workspace_init enqueues a small kernel, never a memset, so both calls may sit
- *     in a captured HIP graph.  No other entry point reads or writes the counters.
- *   - Problems outside the matrix-core kernel (float inputs, row strides beyond its reach) or
- *     with more than 4096 (sequence, KV head, query block) triples run as
- *     ls_hybrid_tree_attn does, in two launches.
- *   - The merging workgroup of a query block works alone, after every other workgroup of that
- *     block has finished: on MI355X this form was slower than the two launches of
- *     ls_hybrid_tree_attn on every shape measured (3x at the 32k-key, 64-node benchmark shape).
- *     It is for callers that must have a single launch; ls_hybrid_tree_attn is the default.
+ *     descriptor.  They must be zero before the first call on a workspace and are left in a
+ *     state the next call accepts: call ls_workspace_init once on a fresh workspace (and again
+ *     after anything else wrote there).  ls_workspace_init enqueues a small kernel, never a
+ *     memset, so both calls may sit in a captured HIP graph.  No other entry point reads or
+ *     writes the counters.  Calls that share a workspace must not overlap in time.
+ *   - Problems outside the matrix-core kernel (float inputs, row strides beyond its reach),
+ *     with more than 64 key splits or with more than 4096 (sequence, KV head, query block)
+ *     triples run as ls_hybrid_tree_attn does, in two launches.
+ *   - ls_set_single_launch_polls(n) sets the number of polls (about half a microsecond
+ *     apart) for later calls of this process: 0 makes every launch the nobody-waits form,
+ *     a negative n restores the default (about 20 ms); n above 2^24 is LS_ERR_SHAPE.  A wait
+ *     that runs out costs time, never correctness.
+ *   - On MI355X this form was slower than the two launches of ls_hybrid_tree_attn on every
+ *     shape measured (1.07x to 1.3x where the workgroups share the merge, 2x and more where
+ *     the last one of a block works alone): it is for callers that must have a single launch.
  */
-#define LS_WORKSPACE_COUNTER_BYTES (4096u * 4u)
+#define LS_WORKSPACE_COUNTER_BYTES (4096u * 24u)
 int ls_workspace_init(void *workspace /* DEVICE, 256-byte aligned */, size_t workspace_bytes, void *stream);
 int ls_hybrid_tree_attn_fused(const ls_desc *desc, const void *q,
                               const void *k_cache, const void *v_cache, const int32_t *prefix_lens,
                               const void *k_tree, const void *v_tree, const int32_t *parents,
                               void *out, float *lse,
                               void *workspace, size_t workspace_bytes, void *stream);
+int ls_set_single_launch_polls(int32_t polls);
 
 /*
  * Unmasked attention of the query rows over the cached keys only, merged over the key

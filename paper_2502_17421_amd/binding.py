@@ -72,6 +72,7 @@ def lib() -> ctypes.CDLL:
     L.ls_hybrid_tree_attn_static.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
     L.ls_hybrid_tree_attn_fused.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_workspace_init.argtypes = [_vp, _sz, _vp]
+    L.ls_set_single_launch_polls.argtypes = [ctypes.c_int32]
     L.ls_cache_attn.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ls_build_tree_mask.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
     L.ls_prefix_attn_splitkv.argtypes = [dp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
@@ -233,7 +234,7 @@ def ls_hybrid_tree_attn_static(desc, q, k_cache, v_cache, prefix_lens, k_tree, v
     return int(st)
 
 
-LS_WORKSPACE_COUNTER_BYTES = 4096 * 4
+LS_WORKSPACE_COUNTER_BYTES = 4096 * 24
 
 
 def ls_workspace_init(workspace, stream=None, check: bool = True) -> int:
@@ -247,13 +248,22 @@ def ls_workspace_init(workspace, stream=None, check: bool = True) -> int:
 
 def ls_hybrid_tree_attn_fused(desc, q, k_cache, v_cache, prefix_lens, k_tree, v_tree, parents, out, lse, workspace,
                               stream=None, check: bool = True) -> int:
-    """The whole path in one launch: the last workgroup of each query block merges (counters at the workspace start)."""
+    """The whole path in one launch: the workgroups of a query block merge its rows between them once all
+    have written their parts (counters at the workspace start; ls_workspace_init before the first call)."""
     st = lib().ls_hybrid_tree_attn_fused(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(prefix_lens),
                                          _ptr(k_tree), _ptr(v_tree), _ptr(parents), _ptr(out), _ptr(lse),
                                          _ptr(workspace), _sz(0 if workspace is None else workspace.numel() *
                                                               workspace.element_size()), _stream(stream))
     if check:
         _check(st, "ls_hybrid_tree_attn_fused")
+    return int(st)
+
+
+def ls_set_single_launch_polls(polls: int, check: bool = True) -> int:
+    """Polls a workgroup of later single-launch calls waits for its query block (0: nobody waits; < 0: default)."""
+    st = lib().ls_set_single_launch_polls(ctypes.c_int32(polls))
+    if check:
+        _check(st, "ls_set_single_launch_polls")
     return int(st)
 
 

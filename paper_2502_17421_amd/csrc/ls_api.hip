@@ -105,7 +105,14 @@ int compute_units()
 
 // The first bytes of every workspace are the arrival counters of the single-launch call, at a
 // place that does not depend on the problem: one ls_workspace_init serves every later call.
-constexpr size_t kArrivalBytes = (size_t)kMaxArrivalCounters * sizeof(uint32_t);
+constexpr size_t kArrivalBytes = (size_t)kMaxArrivalCounters * kCounterWords * sizeof(uint64_t);
+static_assert(kArrivalBytes == LS_WORKSPACE_COUNTER_BYTES, "the header states the size");
+
+// Polls a workgroup of the single-launch call spends waiting for the rest of its (sequence, KV
+// head, query block) before it leaves its rows to the last one: about 20 ms.  Waiting makes sense
+// only when every workgroup of the launch has a compute unit of its own from the start.
+constexpr int32_t kDefaultSpinPolls = 40000;
+int32_t g_spin_polls = -1;  // < 0: the default
 
 struct Workspace {
     size_t off_mask, off_err, off_lse, off_o, total;
@@ -390,10 +397,14 @@ int hybrid_contiguous(const ls_desc *desc, const void *q, const void *k_cache, c
         // Single launch: the last workgroup of each (sequence, KV head, query block) does (c) and (d)
         // for that block's rows; the mask workgroups still fill the workspace's mask and error words.
         const bool fused =
-            single_launch && (int64_t)desc->batch * desc->n_kv_heads * prefix_mfma_query_blocks(p) <= kMaxArrivalCounters;
+            single_launch && plan.n_splits <= 64 &&
+            (int64_t)desc->batch * desc->n_kv_heads * prefix_mfma_query_blocks(p) <= kMaxArrivalCounters;
         FusedTail tail{};
         if (fused) {
-            tail.arrivals = (uint32_t *)base;
+            tail.counters = (uint64_t *)base;
+            const int64_t n_workgroups =
+                (int64_t)desc->batch * desc->n_kv_heads * prefix_mfma_query_blocks(p) * plan.n_splits;
+            tail.spin_limit = n_workgroups <= compute_units() ? (g_spin_polls < 0 ? kDefaultSpinPolls : g_spin_polls) : 0;
             tail.parents = parents;
             tail.out = out;
             for (int i = 0; i < 3; ++i) tail.o_stride[i] = desc->o_stride[i];
@@ -459,8 +470,17 @@ int ls_hybrid_tree_attn_static(const ls_desc *desc, const void *q, const void *k
 int ls_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < kArrivalBytes) return LS_ERR_WORKSPACE;
-    return launch_clear_words((uint32_t *)workspace, kMaxArrivalCounters, (hipStream_t)stream) == hipSuccess ? LS_OK
-                                                                                                          : LS_ERR_HIP;
+    return launch_clear_words((uint32_t *)workspace, (int32_t)(kArrivalBytes / sizeof(uint32_t)), (hipStream_t)stream) ==
+                   hipSuccess
+               ? LS_OK
+               : LS_ERR_HIP;
+}
+
+int ls_set_single_launch_polls(int32_t polls)
+{
+    if (polls > (1 << 24)) return LS_ERR_SHAPE;
+    g_spin_polls = polls;
+    return LS_OK;
 }
 
 int ls_hybrid_tree_attn_fused(const ls_desc *desc, const void *q, const void *k_cache, const void *v_cache,

@@ -65,18 +65,28 @@ struct MaskJob {
     int32_t *err_flag;
 };
 
-// Single-launch form of the whole call: every workgroup of the cached-key kernel counts itself in
-// at arrivals[(sequence, KV head, query block)] after its partial rows are written, and the one
-// that finds all others there does the tree attention and the merge for the rows of that block.
-// Nothing waits for anything.  arrivals == nullptr: the kernel only writes its partial rows.
+// Single-launch form of the whole call.  The workgroups of one (sequence, KV head, query block),
+// one per key split, share three 64-bit words: an arrival word (call number << 32 | workgroups
+// counted in this call) and two claim words used by alternate calls (bit k: the rows of slice k
+// are taken).  A workgroup counts itself in after its partial rows are written and fenced.  The
+// one that completes the count zeroes the other claim word for the next call and adds
+// 2^32 - n_splits to the arrival word: the count is back at zero and the call number has moved,
+// which is what the others poll for, at most spin_limit times.  Whoever sees the move claims
+// slice (its split index) of the block's rows with a fetch-or and does the tree attention and
+// the merge for them; the workgroup that completed the count then claims every slice still free
+// (workgroups that gave up, or all of them when spin_limit is 0) and does those too.  So every
+// row is written exactly once, by the same code whoever writes it, and no wait is unbounded.
+// counters == nullptr: the kernel only writes its partial rows.
 struct FusedTail {
-    uint32_t *arrivals;  // zero before the launch; the merging workgroup puts its counter back to zero
+    uint64_t *counters;  // three words per (sequence, KV head, query block); zero before the first call
     const int32_t *parents;
     void *out;
     int64_t o_stride[3];
     float *lse;
+    int32_t spin_limit;  // polls (about half a microsecond apart) before a workgroup leaves its slice to the last one
 };
 constexpr int kMaxArrivalCounters = 4096;  // (sequence, KV head, query block) triples one single-launch call may have
+constexpr int kCounterWords = 3;           // 64-bit words per triple
 
 struct SplitPlan {
     int32_t n_splits;   // parts the cached-key kernel writes

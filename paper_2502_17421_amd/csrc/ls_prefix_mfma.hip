@@ -249,7 +249,10 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
     const size_t part_row = out.row((size_t)b * p.n_q_heads + hq, split, p.n_tree, ti);
 
     if (k_lo >= k_hi) {  // empty split: weight zero in the merge
-        if (lh == 0 && q_ok) out.lse[part_row] = -INFINITY;
+        if (lh == 0 && q_ok) {
+            if (tail.counters == nullptr) out.lse[part_row] = -INFINITY;
+            else __hip_atomic_store(out.lse + part_row, -INFINITY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         return;
     }
 
@@ -757,9 +760,17 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
             const int ok = __shfl((int)q_ok, row);
             // streaming stores: whole rows that nobody on this compute unit reads again; they leave
             // the L2 as they are written instead of in one burst when the kernel ends
-            if (ok)
-                __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w},
-                                            (u32x4 *)((uint16_t *)out.o + (size_t)prow * D + cpos * 8));
+            uint16_t *dst = (uint16_t *)out.o + (size_t)prow * D + cpos * 8;
+            if (ok && tail.counters == nullptr) {
+                __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, (u32x4 *)dst);
+            } else if (ok) {
+                // single-launch call: device-scope stores, complete in the memory all XCDs share when
+                // the wave's store counter says so (the rows are read by other workgroups of this launch)
+                __hip_atomic_store((uint64_t *)dst, (uint64_t)v.x | ((uint64_t)v.y << 32), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store((uint64_t *)dst + 1, (uint64_t)v.z | ((uint64_t)v.w << 32), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         if (!q_ok) return;
     } else {
@@ -777,44 +788,115 @@ prefix_mfma_kernel(Problem p, SplitPlan plan, Partials out, MaskJob mask_job, Fu
                 *(float4 *)(orow + mt * 32 + 8 * rg + 4 * lh) = v;
             }
     }
-    if (lh == 0) out.lse[part_row] = (m_run * c + log2f(l_tot)) * kLn2;
+    if (lh == 0) {
+        const float lse_part = (m_run * c + log2f(l_tot)) * kLn2;
+        if (tail.counters == nullptr) out.lse[part_row] = lse_part;
+        else __hip_atomic_store(out.lse + part_row, lse_part, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     }();
 
-    if (tail.arrivals == nullptr) return;
-    // ---- single-launch call: count this workgroup in; the last one of its (sequence, KV head,
-    // query block) merges that block's rows.  The fence makes this workgroup's partial rows
-    // visible to the whole device before its count is; the workgroup that reads the full count
-    // fences again before it reads the others' rows.
-    __threadfence();
+    if (tail.counters == nullptr) return;
+    // ---- single-launch call (protocol: see FusedTail).  Memory order: the partial rows and LSEs
+    // were written with device-scope stores; once a wave's store counter is at zero they are in the
+    // memory all XCDs share, so after the barrier a relaxed count says that this workgroup's rows
+    // are there.  (A release fence instead starts a write-back of the XCD's whole L2 in every
+    // workgroup: counting in then took 7.5 us on average and 13.8 us for the last of 256
+    // workgroups, against 1.5 and 2.8.)  The thread that sees the count complete invalidates this
+    // compute unit's view (acquire fence) before the barrier that lets the other waves read.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();  // every wave's rows are out (and nobody uses the staging rows in LDS any more)
-    const int unit = bz * n_qblocks + qblock;
-    volatile uint32_t *seen = (volatile uint32_t *)smem;
-    if (tid == 0)
-        *seen = __hip_atomic_fetch_add(tail.arrivals + unit, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    const bool last = __builtin_amdgcn_readfirstlane(*seen) == (uint32_t)plan.n_splits - 1u;
-    if (!last) return;
-    __threadfence();
-    if (tid == 0) __hip_atomic_store(tail.arrivals + unit, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();  // everybody has read the count: LDS is free again
-    // the tree-mask rows of this sequence, in LDS (at most LS_MAX_TREE rows of 8 words: 32 KB)
+    // LDS from here on: the tree-mask rows of this sequence (at most LS_MAX_TREE rows of 8 words),
+    // its parent array, a few words that carry the counting thread's findings to the others
     uint64_t *mask_rows = (uint64_t *)smem;
-    build_tree_mask_rows(tail.parents + (size_t)b * p.n_tree, p.n_tree, mask_rows, nullptr, tid, NW * 64);
-    // Four rows per wave and step.  When the block is whole query heads, the four are the same tree
-    // node under four heads, which see the same keys; else consecutive rows.
+    int32_t *par_lds = (int32_t *)(smem + LS_MAX_TREE * 8 * sizeof(uint64_t));
+    volatile uint32_t *word = (volatile uint32_t *)(par_lds + LS_MAX_TREE);
+    const int unit = bz * n_qblocks + qblock;
+    const uint32_t n_splits = (uint32_t)plan.n_splits;
+    uint64_t *arrival = tail.counters + (size_t)unit * kCounterWords;
+    // The last wave counts and waits (its first lane); the others build the tree mask meanwhile.
+    const bool counting = tid == (NW - 1) * 64;
+    uint64_t before = 0;
+    if (counting) before = __hip_atomic_fetch_add(arrival, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the parent array goes to LDS (an entry outside {-1} u [0, i) counts as -1)
+    for (int i = tid; i < p.n_tree; i += NW * 64) {
+        const int32_t pa = tail.parents[(size_t)b * p.n_tree + i];
+        par_lds[i] = pa < -1 || pa >= i ? -1 : pa;
+    }
+    __syncthreads();
+    if (counting) {
+        const uint32_t call = (uint32_t)(before >> 32);
+        const bool last = (uint32_t)before == n_splits - 1u;
+        uint64_t *claims = arrival + 1 + (call & 1u);
+        bool go = last;
+        if (last) {
+            __hip_atomic_store(arrival + 1 + ((call + 1u) & 1u), 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(arrival, (1ull << 32) - n_splits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            for (int poll = 0; poll < tail.spin_limit && !go; ++poll) {
+                __builtin_amdgcn_s_sleep(4);
+                go = (uint32_t)(__hip_atomic_load(arrival, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != call;
+            }
+        }
+        uint32_t mine = 0;
+        if (go) {
+            const uint64_t bit = 1ull << split;
+            mine = (__hip_atomic_fetch_or(claims, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit) ? 0u : 1u;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        word[0] = mine;
+        word[1] = last ? 1u : 0u;
+        word[2] = call & 1u;
+    } else if (wave < NW - 1) {
+        // the tree-mask rows, walked in LDS: row i gets bit j iff j is i or an ancestor of i
+        const int words = (p.n_tree + 63) >> 6;
+        for (int node = tid; node < p.n_tree; node += (NW - 1) * 64) {
+            int j = node;
+            for (int w = words - 1; w >= 0; --w) {
+                uint64_t bits = 0;
+                while (j >= 0 && (j >> 6) == w) {
+                    bits |= (uint64_t)1 << (j & 63);
+                    j = par_lds[j];
+                }
+                mask_rows[(size_t)node * words + w] = bits;
+            }
+        }
+    }
+    __syncthreads();
+    const bool mine = __builtin_amdgcn_readfirstlane(word[0]) != 0;
+    const bool last = __builtin_amdgcn_readfirstlane(word[1]) != 0;
+    uint64_t *claims = arrival + 1 + __builtin_amdgcn_readfirstlane(word[2]);
+    if (!mine && !last) return;
+    // A slice is the block's rows cut into n_splits runs; a wave takes one row at a time.
     typedef std::conditional_t<F16, half_t, uint16_t> T16;
     const int row_base = qblock * NW * 32;
     const int rows_here = rows_kv - row_base < NW * 32 ? rows_kv - row_base : NW * 32;
-    const bool whole_heads = row_base % p.n_tree == 0 && rows_here % p.n_tree == 0;
-    const int heads_here = whole_heads ? rows_here / p.n_tree : 1;
-    for (int step = wave; step * 4 < rows_here; step += NW) {
-        int k = step * 4 + (lane >> 4);
-        const bool live = k < rows_here;
-        k = live ? k : rows_here - 1;
-        const int m = whole_heads ? row_base + (k % heads_here) * p.n_tree + k / heads_here : row_base + k;
-        tail_rows<T16, T16, D, 16, 8>(p, mask_rows, out, plan.n_splits, (T16 *)tail.out, tail.o_stride[0],
-                                      tail.o_stride[1], tail.o_stride[2], tail.lse, b, g * p.group + m / p.n_tree,
-                                      m % p.n_tree, live, lane);
+    const int per_slice = (rows_here + (int)n_splits - 1) / (int)n_splits;
+    auto do_slice = [&](int k) {
+        const int hi = (k + 1) * per_slice < rows_here ? (k + 1) * per_slice : rows_here;
+        for (int r = k * per_slice + wave; r < hi; r += NW) {
+            const int m = row_base + r;
+            tail_rows<T16, T16, D, 64, 32>(p, mask_rows, out, plan.n_splits, (T16 *)tail.out, tail.o_stride[0],
+                                           tail.o_stride[1], tail.o_stride[2], tail.lse, b, g * p.group + m / p.n_tree,
+                                           m % p.n_tree, true, lane);
+        }
+    };
+    if (mine) do_slice(split);
+    if (!last) return;
+    // the slices nobody has taken by now
+    __syncthreads();  // everybody has read the words above
+    if (counting) {
+        const uint64_t all = n_splits >= 64u ? ~0ull : (1ull << n_splits) - 1ull;
+        const uint64_t taken = __hip_atomic_fetch_or(claims, all, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t rest = all & ~taken;
+        word[0] = (uint32_t)rest;
+        word[1] = (uint32_t)(rest >> 32);
+    }
+    __syncthreads();
+    uint64_t rest = (uint64_t)__builtin_amdgcn_readfirstlane(word[0]) |
+                    ((uint64_t)__builtin_amdgcn_readfirstlane(word[1]) << 32);
+    while (rest) {
+        do_slice(__builtin_ctzll(rest));
+        rest &= rest - 1;
     }
 }
 
@@ -842,7 +924,8 @@ hipError_t launch_one(const Problem &p, const SplitPlan &plan, const Partials &o
     const int64_t n_main = (int64_t)plan.n_splits * n_qblocks * p.batch * p.n_kv_heads;
     const int64_t n_blocks = n_main + (mask_job.parents ? p.batch : 0);
     if (n_blocks > 0x7fffffff) return hipErrorInvalidValue;
-    if (tail.arrivals && (!out.o_is_16bit || (int64_t)n_qblocks * p.batch * p.n_kv_heads > kMaxArrivalCounters))
+    if (tail.counters && (!out.o_is_16bit || plan.n_splits > 64 ||
+                          (int64_t)n_qblocks * p.batch * p.n_kv_heads > kMaxArrivalCounters))
         return hipErrorInvalidValue;
     hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), lds_bytes, stream, p, plan, out, mask_job,
                        tail, n_qblocks);

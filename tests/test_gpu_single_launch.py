@@ -1,7 +1,9 @@
-"""The single-launch form of the whole call (ls_hybrid_tree_attn_fused: the last workgroup to
-arrive at a query block's counter does the tree attention and the merge) through the C ABI:
-against the CPU oracle, against the two-launch call, and against itself on repeated calls
-(the arrival order changes from call to call, the bits must not).
+"""The single-launch form of the whole call (ls_hybrid_tree_attn_fused: the workgroups of a
+query block count themselves in and merge the block's rows between them, or leave them to the
+one that completes the count) through the C ABI: against the CPU oracle, against the two-launch
+call, against itself on repeated calls (the arrival order changes from call to call, the bits
+must not), and with the bounded wait cut to nothing or next to nothing from the host (every
+row is then still written, by the same code, so the bits must not change either).
 """
 import sys
 
@@ -76,9 +78,24 @@ def test_single_launch_call(name):
             assert np.array_equal(fin, np.isfinite(lse.cpu().numpy()))
             assert np.abs(lse.cpu().numpy()[fin] - lse2[fin]).max() <= 1e-4
     assert runs[0] == runs[1] == runs[2], "repeated single-launch calls differ"
-    # the counters are back at zero
-    head = db.workspace[:ls.LS_WORKSPACE_COUNTER_BYTES].cpu().numpy()
-    assert not head.any()
+    # nobody waits (the workgroup that completes a block's count does all its rows), and a wait
+    # of one poll (most workgroups give up and leave their rows to that one): the same bits
+    try:
+        for polls in (0, 1):
+            ls.ls_set_single_launch_polls(polls)
+            db.out.fill_(float("nan"))
+            db.lse.fill_(float("nan"))
+            out, lse = db.run_fused()
+            torch.cuda.synchronize()
+            assert (bits(out), bits(lse)) == runs[0], f"polls={polls} changes the result"
+    finally:
+        ls.ls_set_single_launch_polls(-1)
+    # the arrival words: count back at zero, call number = calls made, for the blocks the call has
+    words = db.workspace[:ls.LS_WORKSPACE_COUNTER_BYTES].cpu().numpy().view(np.uint64).reshape(-1, 3)
+    assert not (words[:, 0] & np.uint64(0xffffffff)).any()
+    calls = (words[:, 0] >> np.uint64(32)).astype(np.int64)
+    used = int((calls != 0).sum())
+    assert used == 0 or (calls[:used] == 5).all() and not calls[used:].any()
     err = ls.ls_workspace_error(db.desc, db.workspace)
     assert err >= db.workspace.data_ptr()
 
@@ -93,6 +110,11 @@ def test_float_problems_take_two_launches_and_match_bit_for_bit():
     out, lse = db.run_fused()
     torch.cuda.synchronize()
     assert (bits(out), bits(lse)) == b2
+
+
+def test_poll_count_is_bounded():
+    assert ls.ls_set_single_launch_polls((1 << 24) + 1, check=False) == ls.LS_ERR_SHAPE
+    assert ls.ls_set_single_launch_polls(-1, check=False) == ls.LS_OK
 
 
 def test_workspace_init_rejects_a_short_or_missing_workspace():
