@@ -253,6 +253,15 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert L.ls_hybrid_tree_attn_paged(ctypes.byref(f32), one, one, one, one, 64, 16, one, one, one, one, one, one, one, big, None) == ls.LS_ERR_UNSUPPORTED
     assert L.ls_kv_commit_paged(dp, one, one, one, one, one, one, one, None, 64, 16, None, None, None) == ls.LS_ERR_NULL
     assert L.ls_kv_commit_paged(dp, one, one, one, one, one, one, one, one, 64, 24, None, None, None) == ls.LS_ERR_UNSUPPORTED
+    fused = L.ls_hybrid_tree_attn_fused
+    assert fused(dp, one, one, one, None, one, one, one, one, one, one, big, None) == ls.LS_ERR_NULL   # no host-side length
+    assert fused(dp, None, one, one, one, one, one, one, one, one, one, big, None) == ls.LS_ERR_NULL
+    assert fused(dp, one, one, one, one, one, one, one, one, one, one, 16, None) == ls.LS_ERR_WORKSPACE
+    assert L.ls_workspace_init(one, 16, None) == ls.LS_ERR_WORKSPACE
+    assert L.ls_workspace_init(odd, big, None) == ls.LS_ERR_WORKSPACE
+    assert L.ls_set_single_launch_polls((1 << 24) + 1) == ls.LS_ERR_SHAPE
+    assert L.ls_set_single_launch_polls(0) == ls.LS_OK
+    assert L.ls_set_single_launch_polls(-1) == ls.LS_OK
 
 
 def test_binding_raises_when_library_is_missing(tmp_path, monkeypatch):
