@@ -586,8 +586,12 @@ def test_error_budget_of_the_16_bit_partials(name, prefix):
         f"{rms['float partials']:.3e}, bf16 partials {rms['bf16 partials']:.3e}, fused {rms['fused']:.3e}")
     # the fused call computes what the assembled path with bf16 partials computes
     assert np.abs(fused - o16).max() <= 2.0 ** -7 * scale
-    # with float partials what remains is the output rounding plus the bf16 numerators
-    assert e["float partials"] <= floor + 1e-2 * scale / 4
+    # with float partials what remains is the output rounding plus the bf16 numerators: a row's
+    # result is sum p_i v_i / sum p_i with every p_i in the numerator rounded to bf16 (relative
+    # 2^-9) and the denominator not, so it moves by at most 2^-9 max|v| before it is rounded
+    vmax = max(max(float(np.abs(sq.v_cache).max()) if sq.prefix_len else 0.0, float(np.abs(sq.v_tree).max()))
+               for sq in batch.seqs)
+    assert e["float partials"] <= floor + 2.0 ** -9 * vmax * 1.02
     assert e["bf16 partials"] <= 2e-2 * max(1.0, scale) and e["fused"] <= 2e-2 * max(1.0, scale)
     assert rms["float partials"] <= rms["bf16 partials"] * 1.05 + 1e-6
 
