@@ -166,10 +166,21 @@ void *static_scratch_of_current_device()
 
 // Split schedule.  The cached keys of every sequence are cut into pieces of split_len rows
 // (a multiple of 64); the grid is sized for max_prefix_len.  Left to the library, the count S
-// minimises the modelled time of the cached-key kernel: units*S workgroups run in
-// ceil(units*S / slots) rounds of max_prefix_len / S keys each (slots: workgroups resident at
-// once, two per compute unit on the MFMA path), plus a small charge per split for the partial
-// results it adds.
+// minimises a modelled time.  Float path: units*S workgroups run in ceil(units*S / slots)
+// rounds of max_prefix_len / S keys each, plus a small charge per split.  MFMA path: the
+// time of the whole call, cached-key kernel plus the kernel that merges the S parts of every
+// row, from figures measured on MI355X (microseconds; f = share of the compute units the
+// launch occupies, tiles of 32 keys):
+//   kernel = start-up + (rounds - 1) * 5 + rounds * tiles per workgroup * time per tile
+//     query blocks of 256 rows: start-up 8 + 5 f, a tile 0.60 up to f = 1/2 and 0.84 at f = 1
+//       (the matrix cores are power-limited: half the compute units get through a tile in 0.7
+//       of the time that all of them take, so the second half of the chip buys 1.4x, not 2x)
+//     query blocks of 128 rows: start-up 6.7 + 1.8 f, a tile 0.50 up to f = 1/2, 0.66 at f = 1
+//       (the HBM rate)
+//   merge  = 7 + bytes of the partial rows / 3.5 TB/s
+// With it a 2048-row call over 8 KV heads takes 16 splits up to about 12k cached keys and 32
+// beyond 20k (measured: 8k keys 28.9 against 32.2 us, 12k 32.9 against 39.1, 24k 47.9 against
+// 45.7), because every split adds a partial row per query row to write and to merge.
 SplitPlan plan_splits(const ls_desc &d, int32_t request)
 {
     constexpr int kTile = 64;
@@ -188,11 +199,32 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
         if (s_max > 64) s_max = 64;
         if (s_max < 1) s_max = 1;
         double best = 0.0;
+        bool have = false;
         s = 1;
+        const bool mfma = is_16bit(d.dtype);
+        const bool heavy = rows_kv > kPrefixRowsPerWorkgroup / 2;
+        const double rows_total = (double)d.batch * d.n_q_heads * d.n_tree;
         for (int64_t cand = 1; cand <= s_max; ++cand) {
-            const int64_t rounds = (units * cand + slots - 1) / slots;
-            const double cost = (double)rounds / (double)cand + 0.0005 * (double)cand;
-            if (cand == 1 || cost < best - 1e-12) {
+            int64_t len_c = ((max_p + cand - 1) / cand + kTile - 1) / kTile * kTile;
+            if (len_c < kTile) len_c = kTile;
+            int64_t n_c = (max_p + len_c - 1) / len_c;  // the count this candidate ends up with
+            if (n_c < 1) n_c = 1;
+            const int64_t rounds = (units * n_c + slots - 1) / slots;
+            double cost;
+            if (!mfma) {
+                cost = (double)rounds / (double)cand + 0.0005 * (double)cand;
+            } else {
+                const double f = rounds > 1 ? 1.0 : (double)(units * n_c) / (double)slots;
+                const double over = f > 0.5 ? f - 0.5 : 0.0;
+                const double tile = heavy ? 0.60 + 0.48 * over : 0.50 + 0.32 * over;
+                const double start = heavy ? 8.0 + 5.0 * f : 6.7 + 1.8 * f;
+                const double kernel = start + 5.0 * (double)(rounds - 1) + (double)rounds * (double)(len_c / 32) * tile;
+                const double merge = 7.0 + rows_total * (double)n_c * d.head_dim * 2.0 / 3.5e6;
+                cost = kernel + merge;
+            }
+            if (mfma && len_c > kMaxSplitLen && cand < s_max) continue;  // longer than a split may be (below)
+            if (!have || cost < best - 1e-9) {
+                have = true;
                 best = cost;
                 s = cand;
             }

@@ -196,6 +196,17 @@ def test_split_plan_and_workspace_are_stable_and_sane():
     assert n >= parts * 128 * 2 + parts * 4 + 64 * 8 and n % 256 == 0
     z = good_desc(p=0)
     assert ls.ls_prefix_num_splits(z) >= 1 and ls.ls_workspace_bytes(z) > 0
+    # every cache size, both kernels' paths, light and heavy query blocks: the pieces cover the cache
+    # exactly once, none is empty, and none is longer than the matrix-core kernel takes
+    for dtype, dim in ((ls.LS_BF16, 128), (ls.LS_F32, 64)):
+        for hq, hkv, t in ((32, 8, 64), (32, 32, 32), (8, 2, 16)):
+            for p_max in list(range(0, 260)) + [511, 512, 1000, 4096, 8191, 8192, 8193, 12288, 65536, 131072, 1 << 20]:
+                x = good_desc(dtype=dtype, hq=hq, hkv=hkv, d=dim, t=t, p=p_max)
+                n, ln = ls.ls_prefix_num_splits(x), ls.ls_prefix_split_len(x, 0)
+                assert n >= 1 and ln >= 64 and ln % 64 == 0, (dtype, hq, p_max, n, ln)
+                assert (n - 1) * ln < max(p_max, 1) <= n * ln, (dtype, hq, p_max, n, ln)
+                if dtype != ls.LS_F32:
+                    assert ln <= 8192
     bad = good_desc(); bad.head_dim = 80
     with pytest.raises(ls.LsError):
         ls.ls_workspace_bytes(bad)

@@ -261,7 +261,7 @@ def test_full_path_other_shapes(dtype, hq, hkv, d, t, plens):
 @pytest.mark.parametrize("dtype,hq,hkv,d,t,depth,plens", [
     ("bf16", 2, 1, 128, 8, 4, [30000]),       # one KV head, few rows: > 32 parts, a wavefront per row, several batches
     ("bf16", 4, 1, 64, 8, 4, [20000]),        # the same with head_dim 64: 2-byte pieces per lane
-    ("f16", 8, 2, 128, 16, 6, [16000]),       # 17 .. 32 parts, a wavefront per row
+    ("f16", 8, 2, 128, 16, 6, [3000]),        # 17 .. 32 parts, a wavefront per row
     ("bf16", 3, 3, 128, 7, 3, [5000]),        # 21 rows: the last wavefront is part empty; no query grouping
     ("bf16", 10, 2, 128, 300, 40, [1500]),    # five mask words, up to 41 visible keys per row, group of five
     ("bf16", 40, 8, 128, 33, 8, [900, 40]),   # at most four parts, 16 lanes per row
