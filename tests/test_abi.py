@@ -212,6 +212,19 @@ def test_split_plan_and_workspace_are_stable_and_sane():
         ls.ls_workspace_bytes(bad)
 
 
+def test_split_counts_of_the_benchmark_shapes():
+    """The planner's choices for the named workloads on a 256-unit device (what the figures in the
+    design notes were measured with): a change of the model shows up here first."""
+    from paper_2502_17421_amd import synth
+    code = {"bf16": ls.LS_BF16, "f16": ls.LS_F16, "f32": ls.LS_F32}
+    want = {"C2": 16, "C3": 32, "C4": 8, "C5": 8, "D1": 32, "D2": 32, "W1": 4, "H3": 32, "B3": 16, "L3": 8}
+    for name, n in want.items():
+        w = synth.WORKLOADS[name]
+        x = good_desc(dtype=code[w.dtype], b=w.batch, hq=w.n_q_heads, hkv=w.n_kv_heads, d=w.head_dim, t=w.n_tree,
+                      p=w.prefix_hi)
+        assert ls.ls_prefix_num_splits(x) == n, (name, ls.ls_prefix_num_splits(x), n)
+
+
 def test_device_entry_points_reject_bad_arguments_on_the_host():
     """Null pointers, bad descriptors and a short workspace come back as codes; nothing is
     launched, so this runs without a GPU (stream handle 0)."""
