@@ -172,7 +172,7 @@ void *static_scratch_of_current_device()
 // row, from figures measured on MI355X (microseconds; f = share of the compute units the
 // launch occupies, tiles of 32 keys):
 //   kernel = start-up + (rounds - 1) * 5 + rounds * tiles per workgroup * time per tile
-//     query blocks of 256 rows: start-up 8 + 5 f, a tile 0.60 up to f = 1/2 and 0.84 at f = 1
+//     query blocks of 256 rows: start-up 10.5 up to f = 1/2 and 13 at f = 1, a tile 0.60 and 0.84
 //       (the matrix cores are power-limited: half the compute units get through a tile in 0.7
 //       of the time that all of them take, so the second half of the chip buys 1.4x, not 2x)
 //     query blocks of 128 rows: start-up 6.7 + 1.8 f, a tile 0.50 up to f = 1/2, 0.66 at f = 1
@@ -217,13 +217,15 @@ SplitPlan plan_splits(const ls_desc &d, int32_t request)
                 const double f = rounds > 1 ? 1.0 : (double)(units * n_c) / (double)slots;
                 const double over = f > 0.5 ? f - 0.5 : 0.0;
                 const double tile = heavy ? 0.60 + 0.48 * over : 0.50 + 0.32 * over;
-                const double start = heavy ? 8.0 + 5.0 * f : 6.7 + 1.8 * f;
+                const double start = heavy ? 10.5 + 5.0 * over : 6.7 + 1.8 * f;
                 const double kernel = start + 5.0 * (double)(rounds - 1) + (double)rounds * (double)(len_c / 32) * tile;
                 const double merge = 7.0 + rows_total * (double)n_c * d.head_dim * 2.0 / 3.5e6;
                 cost = kernel + merge;
             }
             if (mfma && len_c > kMaxSplitLen && cand < s_max) continue;  // longer than a split may be (below)
-            if (!have || cost < best - 1e-9) {
+            // more splits only for a modelled gain that is more than noise (0.05 us; the float path's
+            // cost is a ratio, of order 1/S)
+            if (!have || cost < best - (mfma ? 0.05 : 1e-9)) {
                 have = true;
                 best = cost;
                 s = cand;

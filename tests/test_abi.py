@@ -217,7 +217,7 @@ def test_split_counts_of_the_benchmark_shapes():
     design notes were measured with): a change of the model shows up here first."""
     from paper_2502_17421_amd import synth
     code = {"bf16": ls.LS_BF16, "f16": ls.LS_F16, "f32": ls.LS_F32}
-    want = {"C2": 16, "C3": 32, "C4": 8, "C5": 8, "D1": 32, "D2": 32, "W1": 4, "H3": 32, "B3": 16, "L3": 8}
+    want = {"C2": 16, "C3": 32, "C4": 8, "C5": 8, "D1": 32, "D2": 32, "W1": 8, "H3": 32, "B3": 16, "L3": 8}
     for name, n in want.items():
         w = synth.WORKLOADS[name]
         x = good_desc(dtype=code[w.dtype], b=w.batch, hq=w.n_q_heads, hkv=w.n_kv_heads, d=w.head_dim, t=w.n_tree,
