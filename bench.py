@@ -28,9 +28,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # WRITE_SIZE runs summarised in profiles/verify_call_C3_mi355x.md, scaled by the copy calibration.
 # Hardware counters cannot be read while this script runs: the figure is copied from that
 # profile and labelled so in the output; None for workloads without a committed profile.
-PROFILED_TRAFFIC_BYTES = {"C3": 138772506 + 18953611,      # fetched + written by the cached-key kernel inside the call
-                          "B3": 164939047 + 10028130, "C5": 746626836 + 47194938, "L3": 151355598 + 18891567,
-                          "C2": 38140343 + 9437729, "C4": 270913212 + 2359584}
+PROFILED_TRAFFIC_BYTES = {"C3": 138772466 + 18883594,      # fetched + written by the cached-key kernel inside the call
+                          "B3": 166267344 + 10028131, "C5": 753731142 + 47194244, "L3": 151355553 + 18883367,
+                          "C2": 38140217 + 9437732, "C4": 270913121 + 2359584}
 PROFILED_TRAFFIC_SOURCE = ("profiles/*.md (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE of the cached-key kernel inside the call, "
                            "scaled by the copy calibration; not this run)")
 PREWARM_SECONDS = 0.35         # untimed calls before --warmup: the shader clock needs ~0.2 s of work to settle
