@@ -100,6 +100,27 @@ def test_single_launch_call(name):
     assert err >= db.workspace.data_ptr()
 
 
+def test_many_calls_in_a_row_agree_bit_for_bit():
+    """The rows one workgroup writes are read by others of the same launch; a row read too early
+    would show up as a changed result (or as the NaN the outputs are filled with) on some call."""
+    batch = synth.make_batch(synth.WORKLOADS["C3"], "peaked", prefix_override=9000)
+    db = DeviceBatch(batch)
+    db.workspace = None
+    out, lse = db.run_fused()
+    torch.cuda.synchronize()
+    ref_out, ref_lse = out.clone(), lse.clone()
+    bad = 0
+    for _ in range(400):
+        db.out.fill_(float("nan"))
+        db.lse.fill_(float("nan"))
+        out, lse = db.run_fused()
+        bad += int(not (torch.equal(out.view(torch.int16), ref_out.view(torch.int16)) and
+                        torch.equal(lse.view(torch.int32), ref_lse.view(torch.int32))))
+    torch.cuda.synchronize()
+    say(f"single launch: 400 calls, {bad} differ from the first")
+    assert bad == 0
+
+
 def test_float_problems_take_two_launches_and_match_bit_for_bit():
     batch = synth.make_batch(synth.WORKLOADS["C1"], "peaked")
     db = DeviceBatch(batch)
